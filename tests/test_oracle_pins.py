@@ -1,0 +1,312 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test states the passage it rests on.  The checks are written with numpy / pure Python in a
+structure different from the oracle's per-token loops (dense matmuls over all experts, subset
+enumeration, library softmax and stable sort), so a dropped term, a wrong sign or index or a
+transposed operand in the oracle fails at least one of them.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy.special import softmax
+
+from oracle import zeda_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_layer(seed, T, H, I, N, Z, scale_r=1.0):
+    r = np.random.default_rng(seed)
+    return dict(
+        x=r.standard_normal((T, H)).astype(np.float32),
+        wr=(scale_r * r.standard_normal((N + Z, H))).astype(np.float32),
+        wg=(r.standard_normal((N, I, H)) / math.sqrt(H)).astype(np.float32),
+        wu=(r.standard_normal((N, I, H)) / math.sqrt(H)).astype(np.float32),
+        wd=(r.standard_normal((N, H, I)) / math.sqrt(I)).astype(np.float32),
+    )
+
+
+def _silu(v):
+    return v / (1.0 + np.exp(-v))
+
+
+def _dense_expert_outputs(L):
+    """Y[e, t, :] = W_d[e] (silu(W_g[e] x_t) * (W_u[e] x_t)) for every expert and token, by matmuls."""
+    x = L["x"].astype(np.float64)
+    g = np.einsum("th,eih->eti", x, L["wg"].astype(np.float64))
+    u = np.einsum("th,eih->eti", x, L["wu"].astype(np.float64))
+    return np.einsum("eti,ehi->eth", _silu(g) * u, L["wd"].astype(np.float64))
+
+
+def _static_topk_moe(x, wr, Y, K, bias=None):
+    """Textbook static top-K MoE (Section 2.1, first formula): softmax, K largest, weights
+    normalised over the K selected, weighted sum of expert outputs Y[e, t, :]."""
+    logits = x.astype(np.float64) @ wr.astype(np.float64).T
+    if bias is not None:
+        logits = logits + bias
+    p = softmax(logits, axis=1)
+    order = np.argsort(-logits.astype(np.float32), axis=1, kind="stable")[:, :K]
+    out = np.zeros((x.shape[0], Y.shape[2]))
+    gates = np.take_along_axis(p, order, axis=1)
+    gates = gates / gates.sum(axis=1, keepdims=True)
+    for t in range(x.shape[0]):
+        for j in range(K):
+            out[t] += gates[t, j] * Y[order[t, j], t]
+    return out, order, gates
+
+
+def test_z0_is_static_topk_moe():
+    # Section 2.1: with no zero experts the dynamic layer is the original y = sum_{i in S} g_i E_i.
+    L = _rand_layer(1, T=9, H=24, I=10, N=6, Z=0)
+    ref, order, gates = _static_topk_moe(L["x"], L["wr"], _dense_expert_outputs(L), K=3)
+    r = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], L["wd"], 6, 0, 3, orc.GATE_TOPK_NORM)
+    assert np.array_equal(r["ids"], order)
+    np.testing.assert_allclose(r["gates"], gates, rtol=1e-12)
+    np.testing.assert_allclose(r["out"], ref, rtol=1e-11, atol=1e-14)
+    assert r["real_slots"] == 9 * 3
+
+
+def test_zero_experts_equal_experts_with_zero_output():
+    # Eq. 1 with the zero experts written out: a static top-K layer over N+N_Z experts whose last
+    # N_Z experts return 0 (Z_j(h) = 0), weights normalised over all K selected and not renormalised
+    # afterwards (Section 4.3.4).
+    N, Z, K = 5, 3, 3
+    L = _rand_layer(2, T=40, H=16, I=6, N=N, Z=Z)
+    Y = _dense_expert_outputs(L)
+    Yaug = np.concatenate([Y, np.zeros((Z,) + Y.shape[1:])], axis=0)
+    ref, order, gates = _static_topk_moe(L["x"], L["wr"], Yaug, K)
+    r = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], L["wd"], N, Z, K, orc.GATE_TOPK_NORM)
+    assert np.array_equal(r["ids"], order)
+    assert (order >= N).any() and (order < N).any()
+    np.testing.assert_allclose(r["out"], ref, rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(r["gates"], gates, rtol=1e-12)
+
+
+def test_bias_enters_logits():
+    N, Z, K = 4, 2, 2
+    L = _rand_layer(3, T=20, H=12, I=5, N=N, Z=Z)
+    bias = np.array([0.3, -0.2, 0.0, 0.7, 1.5, -1.0], dtype=np.float32)
+    Y = np.concatenate([_dense_expert_outputs(L), np.zeros((Z, 20, 12))], axis=0)
+    ref, order, _ = _static_topk_moe(L["x"], L["wr"], Y, K, bias=bias.astype(np.float64))
+    r = orc.moe_forward(L["x"], L["wr"], bias, L["wg"], L["wu"], L["wd"], N, Z, K)
+    assert np.array_equal(r["ids"], order)
+    np.testing.assert_allclose(r["out"], ref, rtol=1e-11, atol=1e-14)
+
+
+def test_all_zero_token_outputs_exact_zero():
+    # Eq. 1: the sum over S~(h) ∩ E is empty when all K slots are zero experts.
+    N, Z, K = 4, 3, 3
+    L = _rand_layer(4, T=6, H=8, I=4, N=N, Z=Z)
+    bias = np.zeros(N + Z, dtype=np.float32)
+    bias[N:] = 1e4
+    r = orc.moe_forward(L["x"], L["wr"], bias, L["wg"], L["wu"], L["wd"], N, Z, K)
+    assert (r["ids"] >= N).all()
+    assert r["real_slots"] == 0
+    assert np.array_equal(r["out"], np.zeros_like(r["out"])) and not np.signbit(r["out"]).any()
+    # the renormalised variant has an empty normaliser there: output is 0 as well
+    r2 = orc.moe_forward(L["x"], L["wr"], bias, L["wg"], L["wu"], L["wd"], N, Z, K, orc.GATE_REAL_RENORM)
+    assert np.array_equal(r2["out"], np.zeros_like(r2["out"]))
+
+
+def test_gate_normalisations():
+    N, Z, K = 6, 4, 4
+    L = _rand_layer(5, T=50, H=16, I=4, N=N, Z=Z)
+    ids_s, g_soft, logits = orc.route(L["x"], L["wr"], None, N, Z, K, orc.GATE_SOFTMAX, want_logits=True)
+    ids_t, g_topk = orc.route(L["x"], L["wr"], None, N, Z, K, orc.GATE_TOPK_NORM)
+    ids_r, g_ren = orc.route(L["x"], L["wr"], None, N, Z, K, orc.GATE_REAL_RENORM)
+    assert np.array_equal(ids_s, ids_t) and np.array_equal(ids_s, ids_r)
+    np.testing.assert_allclose(logits, L["x"].astype(np.float64) @ L["wr"].astype(np.float64).T, rtol=1e-12, atol=1e-13)
+    p = np.take_along_axis(softmax(logits, axis=1), ids_s.astype(np.int64), axis=1)
+    # softmax probabilities untouched
+    np.testing.assert_allclose(g_soft, p, rtol=1e-12)
+    # Section 4.3.4: weights are normalised over the K selected (zero experts included) and the
+    # survivors keep exactly that value: they are not rescaled after the zero slots are removed.
+    np.testing.assert_allclose(g_topk, p / p.sum(axis=1, keepdims=True), rtol=1e-12)
+    np.testing.assert_allclose(g_topk.sum(axis=1), 1.0, rtol=1e-12)
+    real = ids_s < N
+    assert ((g_topk * real).sum(axis=1)[(~real).any(axis=1)] < 1.0).all()
+    # Eq. 7: the renormalised weights sum to one over the active normal experts
+    has_real = real.any(axis=1)
+    np.testing.assert_allclose((g_ren * real).sum(axis=1)[has_real], 1.0, rtol=1e-12)
+    np.testing.assert_allclose(g_ren[real], (p / (p * real).sum(axis=1, keepdims=True))[real], rtol=1e-12)
+    # slots are listed by descending logit
+    sel = np.take_along_axis(logits, ids_s.astype(np.int64), axis=1)
+    assert (np.diff(sel, axis=1) <= 0).all()
+
+
+def test_renorm_output_is_rescaled_default_output():
+    # Eq. 7 = Eq. 1 divided by the sum of the surviving default weights.
+    N, Z, K = 5, 3, 3
+    L = _rand_layer(6, T=30, H=12, I=5, N=N, Z=Z)
+    a = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], L["wd"], N, Z, K, orc.GATE_TOPK_NORM)
+    b = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], L["wd"], N, Z, K, orc.GATE_REAL_RENORM)
+    s = (a["gates"] * (a["ids"] < N)).sum(axis=1)
+    ok = s > 0
+    np.testing.assert_allclose(b["out"][ok], a["out"][ok] / s[ok, None], rtol=1e-11, atol=1e-14)
+
+
+def test_lower_index_wins_ties_and_order():
+    # identical router rows give identical logits: the lower index is selected first
+    N, Z, K = 3, 3, 2
+    L = _rand_layer(7, T=5, H=8, I=4, N=N, Z=Z)
+    L["wr"][:] = L["wr"][0]
+    ids, gates = orc.route(L["x"], L["wr"], None, N, Z, K)
+    assert np.array_equal(ids, np.tile(np.array([0, 1], dtype=np.int32), (5, 1)))
+    np.testing.assert_allclose(gates, 0.5, rtol=1e-12)
+    L["wr"][4] = L["wr"][0] * 3  # row 4 now differs; rows 0,1,2,3,5 still tie
+    ids, _ = orc.route(L["x"], L["wr"], None, N, Z, K)
+    lg = L["x"].astype(np.float64) @ L["wr"].astype(np.float64).T
+    for t in range(5):
+        exp = [4, 0] if lg[t, 4] > lg[t, 0] else [0, 1]
+        assert list(ids[t]) == exp
+
+
+def test_flop_count_matches_eq9_eq10():
+    # Appendix D Eq. 9-10: expert FLOPs = 6 H H_e per (token, normal expert) pair; router 2 (N+N_Z) n H.
+    N, Z, K, T, H, I = 6, 4, 3, 64, 16, 8
+    L = _rand_layer(8, T=T, H=H, I=I, N=N, Z=Z)
+    r = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], L["wd"], N, Z, K)
+    R = int((r["ids"] < N).sum())
+    assert r["real_slots"] == R
+    r_ze = 1.0 - R / (T * K)
+    assert orc.moe_flops(T, H, I, N, Z, K, r_ze) == pytest.approx(6 * H * I * R + 2 * (N + Z) * T * H, rel=1e-12)
+    assert orc.moe_flops(T, H, I, N, 0, K, 0.0) == 6 * K * T * H * I + 2 * N * T * H
+    off, _, _ = orc.dispatch(r["ids"], N)
+    assert off[N] == R
+
+
+def test_table13_theoretical_speedups():
+    # Appendix D Table 13, theoretical columns, from Eq. 14 / Eq. 18 with Table 12's constants.
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "table13_theoretical_speedup.txt")) if l[0] != "#"]
+    assert len(rows) == 8
+    for length, pre, dec in rows:
+        a = 1.0 / orc.flop_ratio(True, float(length), 2048, 4096, 1 / 8, 768, 128, 64, 8, 0.5)
+        b = 1.0 / orc.flop_ratio(False, float(length), 2048, 4096, 1 / 8, 768, 128, 64, 8, 0.5)
+        assert abs(a - float(pre)) <= 5.01e-4, (length, a, pre)
+        assert abs(b - float(dec)) <= 5.01e-4, (length, b, dec)
+
+
+def test_flop_ratio_is_ratio_of_totals():
+    # Eq. 14 is Eq. 13 / Eq. 12: attention (Eq. 11) + MoE (Eq. 9-10) totals, halved and divided by l.
+    l, H, Ha, g, He, N, NZ, K, r = 3000.0, 2048, 4096, 0.125, 768, 128, 64, 8, 0.37
+    attn = 4 * l * l * Ha + 4 * (1 + g) * l * H * Ha
+    ratio = (attn + orc.moe_flops(l, H, He, N, NZ, K, r)) / (attn + orc.moe_flops(l, H, He, N, 0, K, 0.0))
+    assert orc.flop_ratio(True, l, H, Ha, g, He, N, NZ, K, r) == pytest.approx(ratio, rel=1e-12)
+    attn_d = 2 * l * (l - 1) * Ha + 4 * (1 + g) * l * H * Ha  # Eq. 15
+    ratio_d = (attn_d + orc.moe_flops(l, H, He, N, NZ, K, r)) / (attn_d + orc.moe_flops(l, H, He, N, 0, K, 0.0))
+    assert orc.flop_ratio(False, l, H, Ha, g, He, N, NZ, K, r) == pytest.approx(ratio_d, rel=1e-12)
+
+
+def test_brute_force_tiny():
+    # Tiny sizes: the top-K set is the K-subset with the largest logit sum; Eq. 1 evaluated with
+    # python loops, zero-expert terms g_j * 0 written out.
+    T, H, I, N, Z, K = 3, 4, 3, 3, 2, 2
+    L = _rand_layer(9, T=T, H=H, I=I, N=N, Z=Z)
+    r = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], L["wd"], N, Z, K)
+    for t in range(T):
+        x = [float(v) for v in L["x"][t]]
+        logit = [sum(x[h] * float(L["wr"][e, h]) for h in range(H)) for e in range(N + Z)]
+        best = max(itertools.combinations(range(N + Z), K), key=lambda s: sum(logit[e] for e in s))
+        assert set(best) == set(int(i) for i in r["ids"][t])
+        m = max(logit)
+        ex = [math.exp(v - m) for v in logit]
+        p = [v / sum(ex) for v in ex]
+        den = sum(p[e] for e in best)
+        y = [0.0] * H
+        for e in best:
+            if e < N:
+                gv = [sum(float(L["wg"][e, i, h]) * x[h] for h in range(H)) for i in range(I)]
+                uv = [sum(float(L["wu"][e, i, h]) * x[h] for h in range(H)) for i in range(I)]
+                a = [gv[i] / (1 + math.exp(-gv[i])) * uv[i] for i in range(I)]
+                Ey = [sum(float(L["wd"][e, h, i]) * a[i] for i in range(I)) for h in range(H)]
+            else:
+                Ey = [0.0] * H
+            for h in range(H):
+                y[h] += p[e] / den * Ey[h]
+        np.testing.assert_allclose(r["out"][t], y, rtol=1e-11, atol=1e-15)
+
+
+def test_dense_special_case_matches_numpy():
+    # K = N, no zero experts, softmax weights: a dense softmax-weighted mixture, by plain matmuls.
+    N, T, H, I = 4, 11, 10, 6
+    L = _rand_layer(10, T=T, H=H, I=I, N=N, Z=0)
+    r = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], L["wd"], N, 0, N, orc.GATE_SOFTMAX)
+    p = softmax(L["x"].astype(np.float64) @ L["wr"].astype(np.float64).T, axis=1)
+    ref = np.einsum("te,eth->th", p, _dense_expert_outputs(L))
+    np.testing.assert_allclose(r["out"], ref, rtol=1e-11, atol=1e-14)
+
+
+def test_single_expert_function():
+    L = _rand_layer(11, T=2, H=7, I=5, N=2, Z=0)
+    y = orc.expert(L["x"][1], L["wg"][1], L["wu"][1], L["wd"][1])
+    np.testing.assert_allclose(y, _dense_expert_outputs(L)[1, 1], rtol=1e-12, atol=1e-15)
+
+
+def test_copy_expert_identity():
+    # Appendix B: y_copy - y_zero = (sum of the weights of the selected zero-compute experts) * h.
+    N, Z, K = 5, 3, 3
+    L = _rand_layer(12, T=25, H=12, I=5, N=N, Z=Z)
+    a = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], L["wd"], N, Z, K)
+    b = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], L["wd"], N, Z, K, copy_expert=True)
+    zsum = (a["gates"] * (a["ids"] >= N)).sum(axis=1)
+    assert (zsum > 0).any()
+    np.testing.assert_allclose(b["out"] - a["out"], zsum[:, None] * L["x"].astype(np.float64), rtol=1e-10, atol=1e-13)
+
+
+def test_token_permutation_and_scaling_invariants():
+    N, Z, K = 5, 3, 3
+    L = _rand_layer(13, T=20, H=12, I=5, N=N, Z=Z)
+    a = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], L["wd"], N, Z, K, want_y_slot=True)
+    perm = np.random.default_rng(0).permutation(20)
+    b = orc.moe_forward(L["x"][perm], L["wr"], None, L["wg"], L["wu"], L["wd"], N, Z, K)
+    assert np.array_equal(b["out"], a["out"][perm]) and np.array_equal(b["ids"], a["ids"][perm])
+    # scaling W_d of one expert by c scales exactly that expert's terms
+    e, c = 2, 4.0  # a power of two: the scaled fp32 weights are exact
+    wd2 = L["wd"].copy()
+    wd2[e] *= c
+    d = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], wd2, N, Z, K)
+    contrib = np.zeros_like(a["out"])
+    ys = a["y_slot"].reshape(20, K, 12)
+    for t in range(20):
+        for j in range(K):
+            if a["ids"][t, j] == e:
+                contrib[t] += a["gates"][t, j] * ys[t, j]
+    np.testing.assert_allclose(d["out"], a["out"] + (c - 1.0) * contrib, rtol=1e-10, atol=1e-13)
+    # y_slot rows of zero-expert slots are zero
+    assert not ys[a["ids"] >= N].any()
+
+
+def test_dispatch_is_stable_sort_and_combine_recovers_output():
+    N, Z, K, T = 7, 5, 4, 33
+    L = _rand_layer(14, T=T, H=8, I=4, N=N, Z=Z)
+    r = orc.moe_forward(L["x"], L["wr"], None, L["wg"], L["wu"], L["wd"], N, Z, K, want_y_slot=True)
+    ids = r["ids"]
+    off, sorted_slot, slot_to_row = orc.dispatch(ids, N)
+    flat = ids.ravel()
+    real = np.flatnonzero(flat < N)
+    ref_sorted = real[np.argsort(flat[real], kind="stable")]  # library stable sort by expert id
+    R = len(real)
+    assert off[N] == R
+    assert np.array_equal(sorted_slot[:R], ref_sorted) and (sorted_slot[R:] == -1).all()
+    assert np.array_equal(off[:N], np.searchsorted(flat[ref_sorted], np.arange(N), side="left"))
+    inv = np.full(T * K, -1, dtype=np.int32)
+    inv[ref_sorted] = np.arange(R)
+    assert np.array_equal(slot_to_row, inv)
+    for e in range(N):
+        seg = sorted_slot[off[e]:off[e + 1]]
+        assert (flat[seg] == e).all() and (np.diff(seg) > 0).all()
+    # Eq. 1 regrouped: gathering expert-sorted rows back reproduces the forward output
+    y_rows = r["y_slot"][sorted_slot[:R]]
+    out = orc.combine(y_rows, ids, r["gates"], slot_to_row, N)
+    np.testing.assert_allclose(out, r["out"], rtol=1e-12, atol=1e-15)
+
+
+def test_argument_errors():
+    L = _rand_layer(15, T=2, H=4, I=2, N=2, Z=1)
+    with pytest.raises(ValueError):
+        orc.route(L["x"], L["wr"], None, 2, 1, 4)  # K > N + Z
+    with pytest.raises(ValueError):
+        orc.route(L["x"], L["wr"], None, 2, 1, 1, gate_norm=7)
