@@ -1,0 +1,145 @@
+/*
+ * libzeda: forward pass of one ZEDA dynamic-MoE layer on one MI355X (gfx950).
+ *
+ * The layer is the one of Section 2.1 ("Zero-Expert Injection"): a router scores N normal experts
+ * and Z (= N_Z) parameter-free zero experts, the top-K set is taken over all N+Z candidates, and the
+ * output is Eq. 1,
+ *        y~(h) = sum over the selected NORMAL experts i of  g~_i(h) * E_i(h),
+ * so that slots which land on a zero expert cost nothing.  Each normal expert is a gate, an up and a
+ * down projection (Appendix D, Eq. 9: 6*H*H_e FLOPs per token and expert), read here as SwiGLU:
+ *        E_i(h) = W_down[i] * ( silu(W_gate[i] h) .* (W_up[i] h) ).
+ *
+ * Conventions common to every entry point
+ *   - Experts 0..N-1 are normal, N..N+Z-1 are zero experts (their router rows are appended to the
+ *     original ones).  Z = 0 is the static top-K layer.
+ *   - Every pointer is a DEVICE pointer owned by the caller, 16-byte aligned, unless it says "host".
+ *     The library allocates nothing, frees nothing and never synchronises: all work is enqueued on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and the call returns.
+ *   - Matrices are dense row-major with the reduction dimension contiguous:
+ *     x[T,H], w_router[N+Z,H], w_gate[N,I,H], w_up[N,I,H], w_down[N,H,I], out[T,H].
+ *     Their element type is desc->dtype (fp32, or bf16 with fp32 accumulation).  Indices are int32,
+ *     routing weights fp32.
+ *   - Inputs are never written.  Outputs are fully overwritten.
+ *   - Return value: ZEDA_OK, or a negative zeda_status; on error nothing has been enqueued.
+ *   - Calls that share a workspace or output buffer must be ordered by the caller (same stream).
+ *
+ * Shape limits (ZEDA_EUNSUPPORTED otherwise): 1 <= K <= min(N+Z, 16); N+Z <= 256;
+ * T*K < 2^24; bf16: H % 128 == 0 and I % 64 == 0; fp32: H % 4 == 0, I % 4 == 0, H and I <= 12288.
+ */
+#ifndef ZEDA_H
+#define ZEDA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZEDA_OK = 0,
+    ZEDA_EINVAL = -1,       /* NULL required pointer, misaligned pointer, T<0, K<1, K>N+Z, N<1, Z<0, bad enum */
+    ZEDA_EUNSUPPORTED = -2, /* valid layer, outside the shape limits above */
+    ZEDA_EWORKSPACE = -3,   /* workspace smaller than the matching *_workspace_bytes() */
+    ZEDA_EHIP = -4          /* a kernel launch failed (hipGetLastError) */
+} zeda_status;
+
+typedef enum { ZEDA_F32 = 0, ZEDA_BF16 = 1 } zeda_dtype;
+
+/* How the routing weight g~_i of a selected expert is formed from the softmax p over all N+Z logits.
+ * Section 4.3.4: the weights of the surviving normal experts are not renormalised after the zero
+ * experts are removed (TOPK_NORM, the default reading: normalised over all K selected slots, zero
+ * experts included, then zero slots are dropped); Eq. 7 is the renormalised ablation. */
+typedef enum {
+    ZEDA_GATE_SOFTMAX = 0,    /* g = p_i                                                     */
+    ZEDA_GATE_TOPK_NORM = 1,  /* g = p_i / sum of p over the K selected slots (default)      */
+    ZEDA_GATE_REAL_RENORM = 2 /* g = p_i / sum of p over the selected normal experts (Eq. 7) */
+} zeda_gate_norm;
+
+typedef struct {
+    int32_t T;         /* tokens in this call                      */
+    int32_t H;         /* hidden size                              */
+    int32_t I;         /* expert intermediate size (H_e)           */
+    int32_t N;         /* normal experts                           */
+    int32_t Z;         /* zero experts (N_Z), may be 0             */
+    int32_t K;         /* slots per token                          */
+    int32_t dtype;     /* zeda_dtype of x, weights, out            */
+    int32_t gate_norm; /* zeda_gate_norm                           */
+} zeda_layer_desc;
+
+/* Short name of a status code (host pointer to a static string). */
+const char *zeda_status_string(int status);
+
+/* Host-only size queries; 0 if the descriptor is invalid or unsupported.
+ * zeda_workspace_bytes covers zeda_moe_forward and is >= the other two. */
+size_t zeda_workspace_bytes(const zeda_layer_desc *desc);
+size_t zeda_dispatch_workspace_bytes(const zeda_layer_desc *desc);
+size_t zeda_expert_ffn_workspace_bytes(const zeda_layer_desc *desc);
+
+/* Section 2.1, router over the augmented pool E' = E u Z:
+ *   logit[t,e] = <x[t,:], w_router[e,:]> (+ router_bias[e]),  e in [0, N+Z);
+ *   topk_ids[t,0..K) = the K largest logits of token t in descending order (fp32 compare, ties to
+ *   the lower index); topk_gates[t,j] = routing weight of that slot under desc->gate_norm.
+ * router_bias[N+Z] (fp32) may be NULL (the paper's router has none).  T = 0 is a no-op. */
+int zeda_route(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,
+               int32_t *topk_ids /*[T,K]*/, float *topk_gates /*[T,K]*/, void *stream);
+
+/* Zero-slot removal and expert-sorted order (Section 2.1: zero experts contribute no computation).
+ * A slot s = t*K+j is real iff topk_ids[s] < N.  The real slots are listed grouped by expert, and
+ * inside an expert by ascending s:
+ *   expert_offsets[e] = first row of expert e, expert_offsets[N] = R = number of real slots;
+ *   sorted_slot[r] = s for r < R (entries past R are left untouched);
+ *   slot_to_row[s] = r, or -1 for a zero-expert slot;  num_real[0] = R  (r_ZE = 1 - R/(T*K)).
+ * ws: scratch of zeda_dispatch_workspace_bytes(desc). */
+int zeda_dispatch(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t *expert_offsets /*[N+1]*/,
+                  int32_t *sorted_slot /*[T*K]*/, int32_t *slot_to_row /*[T*K]*/, int32_t *num_real /*[1]*/,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/* Grouped SwiGLU expert FFN over the real slots only (Appendix D, Eq. 10: 6*H*I FLOPs per real slot):
+ *   y_slot[r,:] = E_e(x[sorted_slot[r] / K, :])  for expert_offsets[e] <= r < expert_offsets[e+1].
+ * Work is launched for non-empty experts only.  y_slot has room for T*K rows of H elements of
+ * desc->dtype; rows past R are not written.  num_real is read on the device (no host sync).
+ * ws: scratch of zeda_expert_ffn_workspace_bytes(desc) (the activations silu(G).*U). */
+int zeda_expert_ffn(const zeda_layer_desc *desc, const void *x, const void *w_gate, const void *w_up,
+                    const void *w_down, const int32_t *expert_offsets, const int32_t *sorted_slot,
+                    const int32_t *num_real, void *y_slot /*[T*K,H]*/, void *ws, size_t ws_bytes, void *stream);
+
+/* Eq. 1, the weighted sum back in token order, with a fixed summation order and no atomics:
+ *   out[t,:] = sum over j = 0..K-1 with topk_ids[t,j] < N of topk_gates[t,j] * y_slot[slot_to_row[t*K+j], :]
+ * accumulated in fp32 in ascending j.  A token with no real slot gets exact zeros. */
+int zeda_combine(const zeda_layer_desc *desc, const void *y_slot, const int32_t *topk_ids, const float *topk_gates,
+                 const int32_t *slot_to_row, void *out /*[T,H]*/, void *stream);
+
+/* The whole layer: route -> dispatch -> expert FFN -> combine, all on `stream`.
+ * num_real_out[0] (device, may be NULL) receives R.  ws: scratch of zeda_workspace_bytes(desc); after
+ * the call it holds the intermediate results at the offsets zeda_workspace_layout reports. */
+int zeda_moe_forward(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,
+                     const void *w_gate, const void *w_up, const void *w_down, void *out /*[T,H]*/,
+                     int32_t *num_real_out, void *ws, size_t ws_bytes, void *stream);
+
+/* Same as zeda_moe_forward, and records caller-created hipEvent_t handles around the kernels:
+ * events[0] before the first kernel, events[i] after stage i in the order of zeda_stage
+ * (ZEDA_NUM_STAGES + 1 events; host array of handles).  For profiling only. */
+enum {
+    ZEDA_STAGE_ROUTE = 0,
+    ZEDA_STAGE_DISPATCH = 1,
+    ZEDA_STAGE_GATEUP = 2,
+    ZEDA_STAGE_DOWN = 3,
+    ZEDA_STAGE_COMBINE = 4,
+    ZEDA_NUM_STAGES = 5
+};
+int zeda_moe_forward_events(const zeda_layer_desc *desc, const void *x, const void *w_router,
+                            const float *router_bias, const void *w_gate, const void *w_up, const void *w_down,
+                            void *out, int32_t *num_real_out, void *ws, size_t ws_bytes, void *stream,
+                            void *const *events /* host: hipEvent_t[ZEDA_NUM_STAGES + 1] */);
+
+/* Byte offsets inside the forward workspace (host-only).  Returns ZEDA_OK or an error. */
+typedef struct {
+    size_t topk_ids, topk_gates, expert_offsets, sorted_slot, slot_to_row, num_real, dispatch_ws, act, y_slot, total;
+} zeda_ws_layout;
+int zeda_workspace_layout(const zeda_layer_desc *desc, zeda_ws_layout *layout /* host */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZEDA_H */

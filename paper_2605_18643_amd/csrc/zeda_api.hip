@@ -1,0 +1,229 @@
+// C ABI of libzeda: argument validation, workspace carving and the order of the launches.
+// The layer is Eq. 1 of Section 2.1; see include/zeda.h for the meaning of every argument.
+#include "zeda_internal.h"
+
+namespace zeda {
+
+int check_desc(const zeda_layer_desc *d)
+{
+    if (!d) return ZEDA_EINVAL;
+    if (d->T < 0 || d->H < 1 || d->I < 1 || d->N < 1 || d->Z < 0 || d->K < 1) return ZEDA_EINVAL;
+    if ((int64_t)d->K > (int64_t)d->N + d->Z) return ZEDA_EINVAL;
+    if (d->dtype != ZEDA_F32 && d->dtype != ZEDA_BF16) return ZEDA_EINVAL;
+    if (d->gate_norm < ZEDA_GATE_SOFTMAX || d->gate_norm > ZEDA_GATE_REAL_RENORM) return ZEDA_EINVAL;
+    if ((int64_t)d->N + d->Z > kMaxExperts || d->K > kMaxK) return ZEDA_EUNSUPPORTED;
+    if ((int64_t)d->T * d->K >= (1 << 24)) return ZEDA_EUNSUPPORTED;
+    if (d->dtype == ZEDA_BF16) {
+        if (d->H % 128 != 0 || d->I % 64 != 0) return ZEDA_EUNSUPPORTED;
+    } else {
+        if (d->H % 4 != 0 || d->I % 4 != 0 || d->H > 12288 || d->I > 12288) return ZEDA_EUNSUPPORTED;
+    }
+    return ZEDA_OK;
+}
+
+static size_t dispatch_ws_bytes(const zeda_layer_desc *d)
+{
+    const int64_t S = (int64_t)d->T * d->K;
+    const int nb = (int)((S + kCountSlotsPerBlock - 1) / kCountSlotsPerBlock);
+    return align_up((size_t)(nb > 0 ? nb : 1) * d->N * sizeof(int32_t), 256);
+}
+
+static size_t act_bytes(const zeda_layer_desc *d)
+{
+    return align_up((size_t)d->T * d->K * d->I * elt_size(d), 256);
+}
+
+static void layout_of(const zeda_layer_desc *d, zeda_ws_layout *L)
+{
+    const size_t S = (size_t)d->T * d->K;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes ? bytes : 1, 256); return at; };
+    L->topk_ids = take(S * 4);
+    L->topk_gates = take(S * 4);
+    L->expert_offsets = take((size_t)(d->N + 1) * 4);
+    L->sorted_slot = take(S * 4);
+    L->slot_to_row = take(S * 4);
+    L->num_real = take(4);
+    L->dispatch_ws = take(dispatch_ws_bytes(d));
+    L->act = take(act_bytes(d));
+    L->y_slot = take(S * d->H * elt_size(d));
+    L->total = o;
+}
+
+static int forward_impl(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,
+                        const void *w_gate, const void *w_up, const void *w_down, void *out, int32_t *num_real_out,
+                        void *ws, size_t ws_bytes, void *stream, void *const *events)
+{
+    int rc = check_desc(desc);
+    if (rc != ZEDA_OK) return rc;
+    if (!x || !w_router || !w_gate || !w_up || !w_down || !out || !ws) return ZEDA_EINVAL;
+    if (!aligned16(x) || !aligned16(w_router) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) ||
+        !aligned16(out) || !aligned16(ws) || (router_bias && !aligned16(router_bias)))
+        return ZEDA_EINVAL;
+    zeda_ws_layout L;
+    layout_of(desc, &L);
+    if (ws_bytes < L.total) return ZEDA_EWORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char *w = (char *)ws;
+    int32_t *ids = (int32_t *)(w + L.topk_ids);
+    float *gates = (float *)(w + L.topk_gates);
+    int32_t *offsets = (int32_t *)(w + L.expert_offsets);
+    int32_t *sorted_slot = (int32_t *)(w + L.sorted_slot);
+    int32_t *slot_to_row = (int32_t *)(w + L.slot_to_row);
+    int32_t *num_real = (int32_t *)(w + L.num_real);
+    int32_t *hist = (int32_t *)(w + L.dispatch_ws);
+    void *act = w + L.act;
+    void *y_slot = w + L.y_slot;
+
+    auto mark = [&](int i) {
+        if (events && hipEventRecord((hipEvent_t)events[i], s) != hipSuccess) rc = ZEDA_EHIP;
+    };
+    mark(0);
+    if (desc->T == 0) {
+        for (int i = 1; i <= ZEDA_NUM_STAGES; ++i) mark(i);
+        return rc;
+    }
+    if ((rc = launch_route(desc, x, w_router, router_bias, ids, gates, s)) != ZEDA_OK) return rc;
+    mark(1 + ZEDA_STAGE_ROUTE);
+    if ((rc = launch_dispatch(desc, ids, offsets, sorted_slot, slot_to_row, num_real, hist, s)) != ZEDA_OK) return rc;
+    mark(1 + ZEDA_STAGE_DISPATCH);
+    if ((rc = launch_gateup(desc, x, w_gate, w_up, offsets, sorted_slot, act, s)) != ZEDA_OK) return rc;
+    mark(1 + ZEDA_STAGE_GATEUP);
+    if ((rc = launch_down(desc, act, w_down, offsets, y_slot, s)) != ZEDA_OK) return rc;
+    mark(1 + ZEDA_STAGE_DOWN);
+    if ((rc = launch_combine(desc, y_slot, ids, gates, slot_to_row, out, s)) != ZEDA_OK) return rc;
+    mark(1 + ZEDA_STAGE_COMBINE);
+    if (num_real_out) {
+        if (hipMemcpyAsync(num_real_out, num_real, sizeof(int32_t), hipMemcpyDeviceToDevice, s) != hipSuccess)
+            return ZEDA_EHIP;
+    }
+    return rc;
+}
+
+}  // namespace zeda
+
+using namespace zeda;
+
+extern "C" {
+
+const char *zeda_status_string(int status)
+{
+    switch (status) {
+        case ZEDA_OK: return "ZEDA_OK";
+        case ZEDA_EINVAL: return "ZEDA_EINVAL";
+        case ZEDA_EUNSUPPORTED: return "ZEDA_EUNSUPPORTED";
+        case ZEDA_EWORKSPACE: return "ZEDA_EWORKSPACE";
+        case ZEDA_EHIP: return "ZEDA_EHIP";
+        default: return "ZEDA_UNKNOWN";
+    }
+}
+
+size_t zeda_workspace_bytes(const zeda_layer_desc *desc)
+{
+    if (check_desc(desc) != ZEDA_OK) return 0;
+    zeda_ws_layout L;
+    layout_of(desc, &L);
+    return L.total;
+}
+
+size_t zeda_dispatch_workspace_bytes(const zeda_layer_desc *desc)
+{
+    if (check_desc(desc) != ZEDA_OK) return 0;
+    return dispatch_ws_bytes(desc);
+}
+
+size_t zeda_expert_ffn_workspace_bytes(const zeda_layer_desc *desc)
+{
+    if (check_desc(desc) != ZEDA_OK) return 0;
+    return act_bytes(desc);
+}
+
+int zeda_workspace_layout(const zeda_layer_desc *desc, zeda_ws_layout *layout)
+{
+    int rc = check_desc(desc);
+    if (rc != ZEDA_OK) return rc;
+    if (!layout) return ZEDA_EINVAL;
+    layout_of(desc, layout);
+    return ZEDA_OK;
+}
+
+int zeda_route(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,
+               int32_t *topk_ids, float *topk_gates, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != ZEDA_OK) return rc;
+    if (!x || !w_router || !topk_ids || !topk_gates) return ZEDA_EINVAL;
+    if (!aligned16(x) || !aligned16(w_router) || !aligned16(topk_ids) || !aligned16(topk_gates) ||
+        (router_bias && !aligned16(router_bias)))
+        return ZEDA_EINVAL;
+    if (desc->T == 0) return ZEDA_OK;
+    return launch_route(desc, x, w_router, router_bias, topk_ids, topk_gates, (hipStream_t)stream);
+}
+
+int zeda_dispatch(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t *expert_offsets, int32_t *sorted_slot,
+                  int32_t *slot_to_row, int32_t *num_real, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != ZEDA_OK) return rc;
+    if (!topk_ids || !expert_offsets || !sorted_slot || !slot_to_row || !num_real || !ws) return ZEDA_EINVAL;
+    if (!aligned16(topk_ids) || !aligned16(expert_offsets) || !aligned16(sorted_slot) || !aligned16(slot_to_row) ||
+        !aligned16(ws) || (reinterpret_cast<uintptr_t>(num_real) & 3u))
+        return ZEDA_EINVAL;
+    if (ws_bytes < dispatch_ws_bytes(desc)) return ZEDA_EWORKSPACE;
+    return launch_dispatch(desc, topk_ids, expert_offsets, sorted_slot, slot_to_row, num_real, (int32_t *)ws,
+                           (hipStream_t)stream);
+}
+
+int zeda_expert_ffn(const zeda_layer_desc *desc, const void *x, const void *w_gate, const void *w_up,
+                    const void *w_down, const int32_t *expert_offsets, const int32_t *sorted_slot,
+                    const int32_t *num_real, void *y_slot, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != ZEDA_OK) return rc;
+    if (!x || !w_gate || !w_up || !w_down || !expert_offsets || !sorted_slot || !num_real || !y_slot || !ws)
+        return ZEDA_EINVAL;
+    if (!aligned16(x) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) || !aligned16(expert_offsets) ||
+        !aligned16(sorted_slot) || !aligned16(y_slot) || !aligned16(ws))
+        return ZEDA_EINVAL;
+    if (ws_bytes < act_bytes(desc)) return ZEDA_EWORKSPACE;
+    if (desc->T == 0) return ZEDA_OK;
+    // num_real equals expert_offsets[N]; the kernels read the offsets, so R never crosses to the host.
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = launch_gateup(desc, x, w_gate, w_up, expert_offsets, sorted_slot, ws, s)) != ZEDA_OK) return rc;
+    return launch_down(desc, ws, w_down, expert_offsets, y_slot, s);
+}
+
+int zeda_combine(const zeda_layer_desc *desc, const void *y_slot, const int32_t *topk_ids, const float *topk_gates,
+                 const int32_t *slot_to_row, void *out, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != ZEDA_OK) return rc;
+    if (!y_slot || !topk_ids || !topk_gates || !slot_to_row || !out) return ZEDA_EINVAL;
+    if (!aligned16(y_slot) || !aligned16(topk_ids) || !aligned16(topk_gates) || !aligned16(slot_to_row) ||
+        !aligned16(out))
+        return ZEDA_EINVAL;
+    if (desc->T == 0) return ZEDA_OK;
+    return launch_combine(desc, y_slot, topk_ids, topk_gates, slot_to_row, out, (hipStream_t)stream);
+}
+
+int zeda_moe_forward(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,
+                     const void *w_gate, const void *w_up, const void *w_down, void *out, int32_t *num_real_out,
+                     void *ws, size_t ws_bytes, void *stream)
+{
+    return forward_impl(desc, x, w_router, router_bias, w_gate, w_up, w_down, out, num_real_out, ws, ws_bytes, stream,
+                        nullptr);
+}
+
+int zeda_moe_forward_events(const zeda_layer_desc *desc, const void *x, const void *w_router,
+                            const float *router_bias, const void *w_gate, const void *w_up, const void *w_down,
+                            void *out, int32_t *num_real_out, void *ws, size_t ws_bytes, void *stream,
+                            void *const *events)
+{
+    if (!events) return ZEDA_EINVAL;
+    for (int i = 0; i <= ZEDA_NUM_STAGES; ++i)
+        if (!events[i]) return ZEDA_EINVAL;
+    return forward_impl(desc, x, w_router, router_bias, w_gate, w_up, w_down, out, num_real_out, ws, ws_bytes, stream,
+                        events);
+}
+
+}  // extern "C"

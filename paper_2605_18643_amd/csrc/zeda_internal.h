@@ -1,0 +1,44 @@
+// Internal declarations shared by the translation units of libzeda (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "zeda.h"
+
+namespace zeda {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr int kMaxExperts = 256;  // N + Z
+constexpr int kMaxK = 16;
+
+// dispatch geometry (shared by the size query and the launcher)
+constexpr int kCountSlotsPerBlock = 4096;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+int check_desc(const zeda_layer_desc *d);  // ZEDA_OK / ZEDA_EINVAL / ZEDA_EUNSUPPORTED
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t elt_size(const zeda_layer_desc *d) { return d->dtype == ZEDA_BF16 ? 2 : 4; }
+
+// stage launchers: arguments are already validated; each returns ZEDA_OK or ZEDA_EHIP
+int launch_route(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
+                 float *gates, hipStream_t s);
+int launch_dispatch(const zeda_layer_desc *d, const int32_t *ids, int32_t *offsets, int32_t *sorted_slot,
+                    int32_t *slot_to_row, int32_t *num_real, int32_t *block_hist, hipStream_t s);
+int launch_gateup(const zeda_layer_desc *d, const void *x, const void *wg, const void *wu, const int32_t *offsets,
+                  const int32_t *sorted_slot, void *act, hipStream_t s);
+int launch_down(const zeda_layer_desc *d, const void *act, const void *wd, const int32_t *offsets, void *y_slot,
+                hipStream_t s);
+int launch_combine(const zeda_layer_desc *d, const void *y_slot, const int32_t *ids, const float *gates,
+                   const int32_t *slot_to_row, void *out, hipStream_t s);
+
+inline int last_launch_status() { return hipGetLastError() == hipSuccess ? ZEDA_OK : ZEDA_EHIP; }
+
+}  // namespace zeda

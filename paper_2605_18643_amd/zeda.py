@@ -1,0 +1,182 @@
+"""Thin Python binding of libzeda's C ABI (include/zeda.h): argument marshalling only.
+
+Tensors are PyTorch-ROCm device tensors used as plain device buffers; every step of the layer runs
+inside the HIP library.  There is no fallback: if the library is missing, importing the entry points
+raises, and nothing here computes on the CPU.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libzeda.so")
+
+ZEDA_OK, ZEDA_EINVAL, ZEDA_EUNSUPPORTED, ZEDA_EWORKSPACE, ZEDA_EHIP = 0, -1, -2, -3, -4
+ZEDA_F32, ZEDA_BF16 = 0, 1
+GATE_SOFTMAX, GATE_TOPK_NORM, GATE_REAL_RENORM = 0, 1, 2
+STAGES = ("route", "dispatch", "gateup", "down", "combine")
+
+EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_dispatch_workspace_bytes",
+           "zeda_expert_ffn_workspace_bytes", "zeda_workspace_layout", "zeda_route", "zeda_dispatch",
+           "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events")
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "H", "I", "N", "Z", "K", "dtype", "gate_norm")]
+
+
+class WsLayout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_size_t) for n in ("topk_ids", "topk_gates", "expert_offsets", "sorted_slot",
+                                               "slot_to_row", "num_real", "dispatch_ws", "act", "y_slot", "total")]
+
+
+class ZedaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2605_18643_amd.build`")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        dp = ctypes.POINTER(LayerDesc)
+        L.zeda_status_string.restype = ctypes.c_char_p
+        L.zeda_status_string.argtypes = [i32]
+        for name in ("zeda_workspace_bytes", "zeda_dispatch_workspace_bytes", "zeda_expert_ffn_workspace_bytes"):
+            getattr(L, name).restype = sz
+            getattr(L, name).argtypes = [dp]
+        L.zeda_workspace_layout.restype = i32
+        L.zeda_workspace_layout.argtypes = [dp, ctypes.POINTER(WsLayout)]
+        L.zeda_route.restype = i32
+        L.zeda_route.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+        L.zeda_dispatch.restype = i32
+        L.zeda_dispatch.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.zeda_expert_ffn.restype = i32
+        L.zeda_expert_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.zeda_combine.restype = i32
+        L.zeda_combine.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+        L.zeda_moe_forward.restype = i32
+        L.zeda_moe_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.zeda_moe_forward_events.restype = i32
+        L.zeda_moe_forward_events.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(vp)]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().zeda_status_string(int(status)).decode()
+
+
+def make_desc(T, H, I, N, Z, K, dtype, gate_norm=GATE_TOPK_NORM) -> LayerDesc:
+    if isinstance(dtype, torch.dtype):
+        dtype = ZEDA_BF16 if dtype == torch.bfloat16 else ZEDA_F32
+    elif isinstance(dtype, str):
+        dtype = ZEDA_BF16 if dtype == "bf16" else ZEDA_F32
+    return LayerDesc(T, H, I, N, Z, K, int(dtype), int(gate_norm))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != ZEDA_OK:
+        raise ZedaError(rc, where)
+
+
+def workspace_bytes(desc: LayerDesc) -> int:
+    return int(lib().zeda_workspace_bytes(ctypes.byref(desc)))
+
+
+def dispatch_workspace_bytes(desc: LayerDesc) -> int:
+    return int(lib().zeda_dispatch_workspace_bytes(ctypes.byref(desc)))
+
+
+def expert_ffn_workspace_bytes(desc: LayerDesc) -> int:
+    return int(lib().zeda_expert_ffn_workspace_bytes(ctypes.byref(desc)))
+
+
+def workspace_layout(desc: LayerDesc) -> WsLayout:
+    out = WsLayout()
+    _check(lib().zeda_workspace_layout(ctypes.byref(desc), ctypes.byref(out)), "zeda_workspace_layout")
+    return out
+
+
+def zeda_route(desc, x, w_router, router_bias, topk_ids, topk_gates, stream=None) -> None:
+    _check(lib().zeda_route(ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(topk_ids),
+                            _ptr(topk_gates), _stream(stream)), "zeda_route")
+
+
+def zeda_dispatch(desc, topk_ids, expert_offsets, sorted_slot, slot_to_row, num_real, ws, stream=None) -> None:
+    _check(lib().zeda_dispatch(ctypes.byref(desc), _ptr(topk_ids), _ptr(expert_offsets), _ptr(sorted_slot),
+                               _ptr(slot_to_row), _ptr(num_real), _ptr(ws), ws.numel() * ws.element_size(),
+                               _stream(stream)), "zeda_dispatch")
+
+
+def zeda_expert_ffn(desc, x, w_gate, w_up, w_down, expert_offsets, sorted_slot, num_real, y_slot, ws,
+                    stream=None) -> None:
+    _check(lib().zeda_expert_ffn(ctypes.byref(desc), _ptr(x), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+                                 _ptr(expert_offsets), _ptr(sorted_slot), _ptr(num_real), _ptr(y_slot), _ptr(ws),
+                                 ws.numel() * ws.element_size(), _stream(stream)), "zeda_expert_ffn")
+
+
+def zeda_combine(desc, y_slot, topk_ids, topk_gates, slot_to_row, out, stream=None) -> None:
+    _check(lib().zeda_combine(ctypes.byref(desc), _ptr(y_slot), _ptr(topk_ids), _ptr(topk_gates), _ptr(slot_to_row),
+                              _ptr(out), _stream(stream)), "zeda_combine")
+
+
+def zeda_moe_forward(desc, x, w_router, router_bias, w_gate, w_up, w_down, out, num_real_out, ws,
+                     stream=None) -> None:
+    _check(lib().zeda_moe_forward(ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(w_gate),
+                                  _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(num_real_out), _ptr(ws),
+                                  ws.numel() * ws.element_size(), _stream(stream)), "zeda_moe_forward")
+
+
+def zeda_moe_forward_events(desc, x, w_router, router_bias, w_gate, w_up, w_down, out, num_real_out, ws, events,
+                            stream=None) -> None:
+    """`events`: len(STAGES)+1 recorded-once torch.cuda.Event(enable_timing=True) objects."""
+    arr = (ctypes.c_void_p * len(events))(*[ctypes.c_void_p(e.cuda_event) for e in events])
+    _check(lib().zeda_moe_forward_events(ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(router_bias),
+                                         _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(num_real_out),
+                                         _ptr(ws), ws.numel() * ws.element_size(), _stream(stream), arr),
+           "zeda_moe_forward_events")
+
+
+def ws_views(desc: LayerDesc, ws: torch.Tensor):
+    """Typed views of the intermediate results zeda_moe_forward leaves in its workspace."""
+    L = workspace_layout(desc)
+    S = desc.T * desc.K
+    dt = torch.bfloat16 if desc.dtype == ZEDA_BF16 else torch.float32
+    es = 2 if desc.dtype == ZEDA_BF16 else 4
+    b = ws.view(torch.uint8)
+
+    def view(off, n, dtype, size):
+        return b[off: off + n * size].view(dtype)
+
+    return {
+        "topk_ids": view(L.topk_ids, S, torch.int32, 4).view(desc.T, desc.K),
+        "topk_gates": view(L.topk_gates, S, torch.float32, 4).view(desc.T, desc.K),
+        "expert_offsets": view(L.expert_offsets, desc.N + 1, torch.int32, 4),
+        "sorted_slot": view(L.sorted_slot, S, torch.int32, 4),
+        "slot_to_row": view(L.slot_to_row, S, torch.int32, 4),
+        "num_real": view(L.num_real, 1, torch.int32, 4),
+        "act": view(L.act, S * desc.I, dt, es).view(S, desc.I),
+        "y_slot": view(L.y_slot, S * desc.H, dt, es).view(S, desc.H),
+    }

@@ -1,0 +1,93 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded inputs.
+Routing indices and dispatch arrays are compared bit for bit, floating-point results within the stated
+tolerances (tests/gpu_util.py)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import harness, zeda_oracle as orc
+from paper_2605_18643_amd import synth, zeda
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import check_float, desc_of, forward, full_parity  # noqa: E402
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def test_generator_same_bits_on_gpu():
+    k = synth.make_key(42, 1)
+    a = synth.normal_flat(300_000, k, 0.02, "cpu", torch.bfloat16)
+    b = synth.normal_flat(300_000, k, 0.02, "cuda", torch.bfloat16).cpu()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    att = torch.arange(16) % 3
+    w = synth.CONFIGS["c3_qwen_decode"].with_(T=16)
+    assert torch.equal(synth.draw_tokens(w, "cpu", att).float(), synth.draw_tokens(w, "cuda", att).float().cpu())
+
+
+@pytest.mark.parametrize("gate_norm", [zeda.GATE_TOPK_NORM, zeda.GATE_SOFTMAX, zeda.GATE_REAL_RENORM])
+def test_config1_tiny_fp32(gate_norm):
+    w = synth.CONFIGS["c1_tiny_f32"]
+    _say("config 1", w, "gate_norm", gate_norm)
+    L = harness.gapped_layer(w, "cuda", gate_norm=gate_norm)
+    res, st = full_parity(w, L, gate_norm)
+    _say(st)
+    assert st["R"] > 0
+
+
+SMALL_BF16 = [
+    # several token tiles per expert with a ragged tail, zero experts present
+    dict(T=1000, H=256, I=192, N=6, Z=4, K=3, seed=11, zero_bias=0.3),
+    # one expert-row per tile at most, many experts, K=8
+    dict(T=96, H=384, I=128, N=40, Z=24, K=8, seed=12, zero_bias=0.5),
+    # static layer (Z=0), top-1
+    dict(T=257, H=128, I=64, N=5, Z=0, K=1, seed=13, zero_bias=0.0),
+    # the widest router the library accepts, K=16
+    dict(T=130, H=128, I=64, N=200, Z=56, K=16, seed=14, zero_bias=0.2),
+    # decode-sized token counts (the skinny tile configurations)
+    dict(T=20, H=256, I=128, N=12, Z=4, K=4, seed=15, zero_bias=0.4),
+    dict(T=64, H=256, I=128, N=12, Z=4, K=4, seed=16, zero_bias=0.4),
+    dict(T=1, H=256, I=128, N=12, Z=4, K=4, seed=17, zero_bias=0.4),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL_BF16, ids=lambda c: "T%d_H%d_I%d_N%d_Z%d_K%d" % (c["T"], c["H"], c["I"], c["N"], c["Z"], c["K"]))
+def test_small_bf16_layers(cfg):
+    w = synth.Workload("small", dtype="bf16", recipe="zero_bias", x_std=1.0, w_std=0.05, wr_std=0.05, **cfg)
+    _say("small bf16", w)
+    L = harness.gapped_layer(w, "cuda")
+    res, st = full_parity(w, L)
+    _say(st)
+
+
+def test_small_fp32_layer_with_zero_experts_and_ragged_sizes():
+    w = synth.Workload("small_f32", T=77, H=132, I=52, N=7, Z=5, K=3, dtype="f32", seed=21, recipe="zero_bias",
+                       x_std=1.0, w_std=0.08, wr_std=0.08, zero_bias=0.2)
+    _say("small fp32", w)
+    L = harness.gapped_layer(w, "cuda")
+    res, st = full_parity(w, L)
+    _say(st)
+
+
+def test_all_tokens_on_zero_experts_gives_exact_zero_and_no_rows():
+    w = synth.Workload("allzero", T=70, H=128, I=64, N=6, Z=8, K=4, dtype="bf16", seed=31, recipe="zero_bias",
+                       zero_bias=50.0)
+    L = harness.gapped_layer(w, "cuda")
+    res = forward(w, L)
+    assert int(res["num_real"].item()) == 0 and not res["expert_offsets"].numpy().any()
+    assert (res["slot_to_row"].numpy() == -1).all()
+    assert not res["out"].float().numpy().any()
+    assert (res["topk_ids"].numpy() >= w.N).all()
+
+
+def test_forward_is_deterministic():
+    w = synth.Workload("det", T=700, H=256, I=128, N=9, Z=5, K=4, dtype="bf16", seed=41, recipe="zero_bias", zero_bias=0.3)
+    L = synth.make_layer(w, "cuda")
+    a, b = forward(w, L), forward(w, L)
+    for k in ("topk_ids", "topk_gates", "expert_offsets", "slot_to_row", "out"):
+        assert torch.equal(a[k].view(torch.uint8), b[k].view(torch.uint8)), k
+    R = int(a["num_real"].item())
+    assert torch.equal(a["sorted_slot"][:R], b["sorted_slot"][:R])
+    assert torch.equal(a["y_slot"][:R].view(torch.int16), b["y_slot"][:R].view(torch.int16))
