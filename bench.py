@@ -1,0 +1,152 @@
+#!/usr/bin/env python3
+"""Benchmark of the ZEDA MoE-layer forward path on one MI355X.
+
+One step = one zeda_moe_forward over the Qwen3-30B-A3B-shaped prefill layer (T=4096, H=2048, I=768,
+N=128 normal + Z=32 zero experts, K=8, bf16, about half of the slots on zero experts), inputs resident
+in HBM.  Prints ONE JSON line: tokens/s, the roofline of the dominant kernel (gate/up grouped GEMM)
+from HIP-event timings taken in this run, and the CPU oracle timed on the host cores beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2605_18643_amd import synth, zeda  # noqa: E402
+
+METRIC = "MoE-layer tokens/s (Qwen3-30B-A3B shape, ~50% zero slots) + MFMA util %"
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def run_layer(w: synth.Workload, L, steps: int, warmup: int):
+    """Times `steps` forward passes (whole-path wall time) and, in a second loop of the same length,
+    each stage with HIP events recorded between the kernels on the launch stream."""
+    d = zeda.make_desc(w.T, w.H, w.I, w.N, w.Z, w.K, w.dtype)
+    ws = torch.empty(zeda.workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    out = torch.empty((w.T, w.H), dtype=w.torch_dtype, device="cuda")
+    nreal = torch.zeros(1, dtype=torch.int32, device="cuda")
+    args = (d, L["x"], L["w_router"], L["router_bias"], L["w_gate"], L["w_up"], L["w_down"], out, nreal, ws)
+    for _ in range(warmup):
+        zeda.zeda_moe_forward(*args)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        zeda.zeda_moe_forward(*args)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    n_ev = len(zeda.STAGES) + 1
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in range(steps)]
+    for row in evs:
+        for e in row:
+            e.record()  # creates the underlying hipEvent_t
+    torch.cuda.synchronize()
+    for row in evs:
+        zeda.zeda_moe_forward_events(*args, row)
+    torch.cuda.synchronize()
+    stage_ms = np.zeros(len(zeda.STAGES))
+    for row in evs:
+        for i in range(len(zeda.STAGES)):
+            stage_ms[i] += row[i].elapsed_time(row[i + 1])
+    stage_ms /= steps
+    v = zeda.ws_views(d, ws)
+    off = v["expert_offsets"].cpu().numpy()
+    R = int(nreal.item())
+    return {"wall_s": wall, "stage_ms": stage_ms, "R": R, "nonempty": int((np.diff(off) > 0).sum()),
+            "max_rows": int(np.diff(off).max()), "out": out}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2_qwen_prefill", choices=sorted(synth.CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-z0", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (the HIP library has no CPU fallback)", file=sys.stderr)
+        return 2
+    zeda.lib()
+
+    w = synth.CONFIGS[a.workload]
+    L = synth.make_layer(w, "cuda")
+    torch.cuda.synchronize()
+    r = run_layer(w, L, a.steps, a.warmup)
+    ms = r["wall_s"] / a.steps * 1e3
+    tokens_per_s = w.T * a.steps / r["wall_s"]
+
+    es = 2 if w.dtype == "bf16" else 4
+    R, ne = r["R"], r["nonempty"]
+    stage = dict(zip(zeda.STAGES, (float(x) for x in r["stage_ms"])))
+    # gate/up grouped GEMM: weights of the non-empty experts once, one x row in and one act row out per real slot
+    gu_bytes = 2.0 * w.H * w.I * es * ne + R * (w.H + w.I) * es
+    gu_flops = 4.0 * w.H * w.I * R
+    dn_bytes = 1.0 * w.H * w.I * es * ne + R * (w.I + w.H) * es
+    dn_flops = 2.0 * w.H * w.I * R
+    gu_s, dn_s = stage["gateup"] * 1e-3, stage["down"] * 1e-3
+    achieved_gbs = gu_bytes / gu_s / 1e9
+    roofline = {"kernel": "ffn_bf16_kernel<gate/up>", "bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": None,
+                "avg_launch_us": gu_s * 1e6, "algorithmic_bytes": gu_bytes}
+    ffn_tflops = (gu_flops + dn_flops) / (gu_s + dn_s) / 1e12
+    res = {
+        "metric": METRIC, "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "T": w.T, "H": w.H, "I": w.I, "N": w.N, "Z": w.Z, "K": w.K,
+                   "real_slots": R, "r_ze": 1.0 - R / (w.T * w.K), "nonempty_experts": ne, "max_rows_per_expert": r["max_rows"]},
+        "roofline": roofline,
+        "mfma_util_pct": 100.0 * ffn_tflops / MFMA_BF16_PEAK_TFLOPS,
+        "expert_gemm": {"tflops": ffn_tflops, "peak_tflops": MFMA_BF16_PEAK_TFLOPS,
+                        "gateup_tflops": gu_flops / gu_s / 1e12, "down_tflops": dn_flops / dn_s / 1e12,
+                        "down_gbs": dn_bytes / dn_s / 1e9},
+        "stage_us": {k: v * 1e3 for k, v in stage.items()},
+    }
+
+    if not a.no_z0 and w.Z > 0:
+        # the same kernels on the static layer: no zero experts, top-K over the N normal experts only
+        w0 = w.with_(Z=0, recipe="plain")
+        L0 = dict(L)
+        L0["w_router"] = L["w_router"][: w.N].contiguous()
+        L0["router_bias"] = None
+        r0 = run_layer(w0, L0, a.steps, a.warmup)
+        res["z0"] = {"ms_per_step": r0["wall_s"] / a.steps * 1e3, "speedup_vs_z0": r0["wall_s"] / r["wall_s"],
+                     "real_slots": r0["R"], "expert_flop_reduction": 1.0 - R / max(1, r0["R"]),
+                     "stage_us": {k: float(v) * 1e3 for k, v in zip(zeda.STAGES, r0["stage_ms"])}}
+
+    if not a.no_cpu_baseline:
+        from oracle import harness, zeda_oracle as orc  # CPU-baseline leg only
+
+        arrays = harness.to_arrays(L)
+        n_tok = min(w.T, 4096)
+        tok = np.arange(n_tok)
+        t0 = time.perf_counter()
+        ref = harness.oracle_forward(w, arrays, tokens=tok)
+        dt = time.perf_counter() - t0
+        got = r["out"][:n_tok].float().cpu().numpy()
+        res["cpu_baseline"] = {"value": n_tok / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"first {n_tok} of {w.T} tokens of {w.name}, one pass, {dt:.1f} s",
+                               "gpu_vs_oracle_rel_l2": harness.rel_l2(got, ref["out"])}
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

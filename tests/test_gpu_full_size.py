@@ -1,0 +1,62 @@
+"""GPU parity at the full BASELINE sizes, in the launch configuration bench.py times.
+Routing and dispatch are checked on every token; the oracle's expert arithmetic runs on all tokens where it
+finishes in seconds (configs 2 and 3) and on a sample of tokens at T=16384 (config 4)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import harness
+from paper_2605_18643_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import full_parity  # noqa: E402
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def test_config3_decode_full():
+    w = synth.CONFIGS["c3_qwen_decode"]
+    _say("config 3", w)
+    L = harness.gapped_layer(w, "cuda")
+    res, st = full_parity(w, L)
+    _say(st)
+    assert 0.35 < st["r_ze"] < 0.65 and st["nonempty"] < w.N
+
+
+def test_config2_prefill_full():
+    w = synth.CONFIGS["c2_qwen_prefill"]
+    _say("config 2", w)
+    L = harness.gapped_layer(w, "cuda")
+    _say("redrawn tokens:", L["redrawn"])
+    res, st = full_parity(w, L)
+    _say(st)
+    assert abs(st["r_ze"] - 0.5) < 0.02 and st["nonempty"] == w.N
+
+
+def test_config2_static_layer_z0():
+    # the Z=0 layer the speedup is quoted against: same weights, router restricted to the normal experts
+    w = synth.CONFIGS["c2_qwen_prefill"].with_(Z=0, recipe="plain", T=1024)
+    _say("config 2 at Z=0", w)
+    L = harness.gapped_layer(w, "cuda")
+    res, st = full_parity(w, L, tokens=np.arange(0, w.T, 4))
+    _say(st)
+    assert st["R"] == w.T * w.K
+
+
+def test_config4_hetero_prefill_sampled():
+    w = synth.CONFIGS["c4_hetero_prefill"]
+    _say("config 4", w)
+    L = harness.gapped_layer(w, "cuda")
+    _say("redrawn tokens:", L["redrawn"])
+    tokens = np.sort(np.random.default_rng(0).choice(w.T, size=192, replace=False))
+    res, st = full_parity(w, L, tokens=tokens)
+    _say(st)
+    zc = (res["topk_ids"].numpy() >= w.N).sum(axis=1)
+    hist = np.bincount(zc, minlength=9) / w.T
+    assert abs(hist[6:9].sum() - 0.6) < 0.02 and abs(hist[0:2].sum() - 0.4) < 0.02
+    load = np.diff(res["expert_offsets"].numpy())
+    _say("rows per expert: max", load.max(), "min", load.min(), "empty", int((load == 0).sum()))
+    assert load.max() > 8 * load.mean()
