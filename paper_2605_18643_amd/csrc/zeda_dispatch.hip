@@ -94,7 +94,10 @@ __global__ __launch_bounds__(kPlaceThreads) void dispatch_place_kernel(const int
     // contiguous segment of this wave, in groups of 256 slots (4 consecutive slots per lane)
     const int groups = (S + 255) / 256;
     const int gpw = (groups + kPlaceWaves - 1) / kPlaceWaves;
-    const int g0 = wave * gpw, g1 = min(groups, g0 + gpw);
+    // every workgroup reads the whole id list: each starts at a different segment so that they do not all
+    // queue on the same L2 channel at the same time (segment seg is still placed after segments < seg)
+    const int seg = (wave + e) % kPlaceWaves;
+    const int g0 = seg * gpw, g1 = min(groups, g0 + gpw);
     const int4 *ids4 = reinterpret_cast<const int4 *>(ids);
     const int full4 = S / 4;  // int4 loads are in bounds below this index
 
@@ -110,36 +113,53 @@ __global__ __launch_bounds__(kPlaceThreads) void dispatch_place_kernel(const int
         return v;
     };
 
+    // The segment is walked in batches of kBatch groups whose loads are all issued before any is used.
+    // When the whole segment is one batch (the usual case) the ids stay in registers for the second pass.
+    constexpr int kBatch = 8;
+    const bool one_batch = gpw <= kBatch;
+    int4 keep[kBatch];
     int my = 0;
-    for (int g = g0; g < g1; ++g) {
-        int4 v = load4(g);
-        my += (v.x == e) + (v.y == e) + (v.z == e) + (v.w == e);
+    for (int gb = g0; gb < g1; gb += kBatch) {
+        int4 v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) v[u] = (gb + u < g1) ? load4(gb + u) : make_int4(-1, -1, -1, -1);
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            my += (v[u].x == e) + (v[u].y == e) + (v[u].z == e) + (v[u].w == e);
+            keep[u] = v[u];
+        }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) my += __shfl_xor(my, off);
-    if (lane == 0) wave_cnt[wave] = my;
+    if (lane == 0) wave_cnt[seg] = my;
     __syncthreads();
     int before = first_row;
-    for (int w = 0; w < wave; ++w) before += wave_cnt[w];
+    for (int w = 0; w < seg; ++w) before += wave_cnt[w];
 
-    for (int g = g0; g < g1; ++g) {
-        int4 v = load4(g);
-        const bool hx = v.x == e, hy = v.y == e, hz = v.z == e, hw = v.w == e;
-        const int mine = hx + hy + hz + hw;
-        // matches in lower lanes of this group
-        int incl = mine;
+    for (int gb = g0; gb < g1; gb += kBatch) {
+        int4 v[kBatch];
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            int o = __shfl_up(incl, off);
-            if (lane >= off) incl += o;
+        for (int u = 0; u < kBatch; ++u)
+            v[u] = one_batch ? keep[u] : ((gb + u < g1) ? load4(gb + u) : make_int4(-1, -1, -1, -1));
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const bool hx = v[u].x == e, hy = v[u].y == e, hz = v[u].z == e, hw = v[u].w == e;
+            const int mine = hx + hy + hz + hw;
+            // matches in lower lanes of this group
+            int incl = mine;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                int o = __shfl_up(incl, off);
+                if (lane >= off) incl += o;
+            }
+            int r = before + incl - mine;
+            const int s = ((gb + u) * 64 + lane) * 4;
+            if (hx) { sorted_slot[r] = s + 0; slot_to_row[s + 0] = r; ++r; }
+            if (hy) { sorted_slot[r] = s + 1; slot_to_row[s + 1] = r; ++r; }
+            if (hz) { sorted_slot[r] = s + 2; slot_to_row[s + 2] = r; ++r; }
+            if (hw) { sorted_slot[r] = s + 3; slot_to_row[s + 3] = r; ++r; }
+            before += __shfl(incl, 63);
         }
-        int r = before + incl - mine;
-        const int s = (g * 64 + lane) * 4;
-        if (hx) { sorted_slot[r] = s + 0; slot_to_row[s + 0] = r; ++r; }
-        if (hy) { sorted_slot[r] = s + 1; slot_to_row[s + 1] = r; ++r; }
-        if (hz) { sorted_slot[r] = s + 2; slot_to_row[s + 2] = r; ++r; }
-        if (hw) { sorted_slot[r] = s + 3; slot_to_row[s + 3] = r; ++r; }
-        before += __shfl(incl, 63);
     }
 }
 

@@ -8,17 +8,6 @@ namespace zeda {
 constexpr int kRouteTokens = 32;  // tokens per workgroup of the bf16 kernel (one MFMA column block)
 constexpr int kRouteThreads = 256;
 
-// (value, index) butterfly: every lane ends with the maximum value, ties to the lower index.
-__device__ __forceinline__ void wave_argmax(float &v, int &i)
-{
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        float ov = __shfl_xor(v, off);
-        int oi = __shfl_xor(i, off);
-        if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
-    }
-}
-
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
@@ -26,61 +15,127 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// Selection and gates for one token, executed by one wave.  `row` points at the token's NE fp32
-// logits in LDS.  Lane c-th candidate is expert lane + 64*c.
-__device__ __forceinline__ void select_token(const float *row, int NE, int N, int K, int gate_norm, int32_t *ids_out,
-                                             float *gates_out)
+// Selection and gates for NT tokens at once (tokens base, base+4, ... of the workgroup's block, whose
+// fp32 logits are rows of lg in LDS), executed by one wave.  The c-th candidate of a lane is expert lane + 64*c.  The NT reduction
+// chains are independent and written side by side so that their cross-lane exchanges overlap.
+template <int NT>
+__device__ __forceinline__ void select_tokens(const float *lg, int LD, int base, int ntok, int t0, int T, int NE, int N,
+                                              int K, int gate_norm, int32_t *__restrict__ ids, float *__restrict__ gates)
 {
     const int lane = threadIdx.x & 63;
-    float cand[4];
+    bool ok[NT];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        int e = lane + 64 * c;
-        cand[c] = e < NE ? row[e] : -INFINITY;
+    for (int i = 0; i < NT; ++i) ok[i] = base + 4 * i < ntok && t0 + base + 4 * i < T;
+    float cand[NT][4], all_max[NT], all_sum[NT], my_logit[NT];
+    int my_id[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            int e = lane + 64 * c;
+            cand[i][c] = (ok[i] && e < NE) ? lg[(base + 4 * i) * LD + e] : -INFINITY;
+        }
+        all_max[i] = fmaxf(fmaxf(cand[i][0], cand[i][1]), fmaxf(cand[i][2], cand[i][3]));
+        my_id[i] = 0;
+        my_logit[i] = -INFINITY;
+        all_sum[i] = 0.f;
     }
-    float all_max = fmaxf(fmaxf(cand[0], cand[1]), fmaxf(cand[2], cand[3]));
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) all_max = fmaxf(all_max, __shfl_xor(all_max, off));
-    float all_sum = 0.f;
+    for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+        for (int i = 0; i < NT; ++i) all_max[i] = fmaxf(all_max[i], __shfl_xor(all_max[i], off));
     if (gate_norm == ZEDA_GATE_SOFTMAX) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) all_sum += (lane + 64 * c < NE) ? expf(cand[c] - all_max) : 0.f;
-        all_sum = wave_sum(all_sum);
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) all_sum[i] += (lane + 64 * c < NE) ? expf(cand[i][c] - all_max[i]) : 0.f;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+            for (int i = 0; i < NT; ++i) all_sum[i] += __shfl_xor(all_sum[i], off);
     }
-    int my_id = 0;
-    float my_logit = -INFINITY;
     for (int j = 0; j < K; ++j) {
-        float bv = cand[0];
-        int bi = lane;
+        float bv[NT];
+        int bi[NT];
 #pragma unroll
-        for (int c = 1; c < 4; ++c)
-            if (cand[c] > bv) { bv = cand[c]; bi = lane + 64 * c; }
-        wave_argmax(bv, bi);
-        if ((bi & 63) == lane) {
+        for (int i = 0; i < NT; ++i) {
+            bv[i] = cand[i][0];
+            bi[i] = lane;
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if ((bi >> 6) == c) cand[c] = -INFINITY;
+            for (int c = 1; c < 4; ++c)
+                if (cand[i][c] > bv[i]) { bv[i] = cand[i][c]; bi[i] = lane + 64 * c; }
         }
-        if (lane == j) { my_id = bi; my_logit = bv; }
+        // (value, index) butterfly: every lane ends with the maximum value, ties to the lower index
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+            for (int i = 0; i < NT; ++i) {
+                float ov = __shfl_xor(bv[i], off);
+                int oi = __shfl_xor(bi[i], off);
+                if (ov > bv[i] || (ov == bv[i] && oi < bi[i])) { bv[i] = ov; bi[i] = oi; }
+            }
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            if ((bi[i] & 63) == lane) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if ((bi[i] >> 6) == c) cand[i][c] = -INFINITY;
+            }
+            if (lane == j) { my_id[i] = bi[i]; my_logit[i] = bv[i]; }
+        }
     }
     // lanes 0..K-1 hold the slots in descending-logit order
     const bool slot = lane < K;
-    float ex = slot ? expf(my_logit - all_max) : 0.f;
-    float denom;
-    if (gate_norm == ZEDA_GATE_SOFTMAX) denom = all_sum;
-    else if (gate_norm == ZEDA_GATE_TOPK_NORM) denom = wave_sum(ex);
-    else denom = wave_sum((slot && my_id < N) ? ex : 0.f);
-    if (slot) {
-        ids_out[lane] = my_id;
-        gates_out[lane] = denom > 0.f ? ex / denom : 0.f;
+    float ex[NT], denom[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        ex[i] = slot ? expf(my_logit[i] - all_max[i]) : 0.f;
+        denom[i] = gate_norm == ZEDA_GATE_TOPK_NORM ? ex[i] : ((slot && my_id[i] < N) ? ex[i] : 0.f);
+    }
+    if (gate_norm != ZEDA_GATE_SOFTMAX) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+            for (int i = 0; i < NT; ++i) denom[i] += __shfl_xor(denom[i], off);
+    }
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        const float dn = gate_norm == ZEDA_GATE_SOFTMAX ? all_sum[i] : denom[i];
+        if (slot && ok[i]) {
+            const size_t o = (size_t)(t0 + base + 4 * i) * K + lane;
+            ids[o] = my_id[i];
+            gates[o] = dn > 0.f ? ex[i] / dn : 0.f;
+        }
     }
 }
 
-// bf16 router.  A workgroup owns kRouteTokens tokens and all NE experts; its 4 waves split the hidden
-// dimension, each accumulating NB 32x32 MFMA blocks (experts are MFMA rows, tokens MFMA columns), then
-// the partial sums are added in LDS in wave order and each wave selects for 8 tokens.
-// Inside every 64-wide k chunk lane half h and step s read elements 32h+8s..+8 of both operands: the
-// sum over k does not depend on the order, and each lane then walks 64 contiguous bytes.
+// The tokens tk = wave, wave + 4, ... < ntok of a workgroup, NT at a time.
+template <int NT>
+__device__ __forceinline__ void select_block(const float *lg, int LD, int ntok, int t0, int T, int NE, int N, int K,
+                                             int gate_norm, int32_t *__restrict__ ids, float *__restrict__ gates)
+{
+    const int wave = threadIdx.x >> 6;
+    for (int base = wave; base < ntok; base += 4 * NT)
+        select_tokens<NT>(lg, LD, base, ntok, t0, T, NE, N, K, gate_norm, ids, gates);
+}
+
+// bf16 router.  A workgroup owns kRouteTokens tokens and all NE experts (NB MFMA row blocks of 32; tokens
+// are the MFMA columns).  x rows and router rows stream through a kRouteStages-deep LDS ring in 64-wide
+// k chunks with global->LDS loads, 128-byte rows whose 16-byte pieces are XOR-permuted by the row index
+// (applied on the global address) so that fragment reads spread over the banks; a counted s_waitcnt and
+// one s_barrier per chunk order the ring.  The four waves split the four 16-wide MFMA steps of every
+// chunk, so each holds a partial sum over a quarter of the hidden dimension; the partial sums are added
+// in LDS in wave order (a fixed order: the logits are reproducible), then each wave selects for 8 tokens.
+constexpr int kRouteStages = 4;
+
+__device__ __forceinline__ int route_swz(int row, int piece) { return piece ^ ((row >> 1) & 7); }
+
+template <int N>
+__device__ __forceinline__ void route_wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 template <int NB>
 __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t *__restrict__ x,
                                                                    const bf16_t *__restrict__ wr,
@@ -89,15 +144,41 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
                                                                    int32_t *__restrict__ ids, float *__restrict__ gates)
 {
     constexpr int LD = NB * 32 + 1;
-    __shared__ float lg[kRouteTokens * LD];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int ROWS = kRouteTokens + 32 * NB;  // rows of one ring slot: tokens first, then router rows
+    constexpr int STAGE = ROWS * 128;
+    constexpr int NL = 1 + NB;                    // wave load instructions (8 rows each) per chunk and wave
+    static_assert(kRouteTokens == 32 && kRouteThreads == 256, "one token block, four waves");
+    static_assert(kRouteTokens * LD * 4 <= kRouteStages * STAGE, "the logits reuse the ring");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    float *lg = reinterpret_cast<float *>(lds);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int t0 = blockIdx.x * kRouteTokens;
     const int col = lane & 31, half = lane >> 5;
-    // 64-wide k chunks are dealt to the four waves round-robin (H is a multiple of 64)
-    const bf16_t *xrow = x + (size_t)min(t0 + col, T - 1) * H + half * 32;
-    const bf16_t *wrow[NB];
+
+    const bf16_t *src[NL];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) wrow[b] = wr + (size_t)min(b * 32 + col, NE - 1) * H + half * 32;
+    for (int i = 0; i < NL; ++i) {
+        const int row = (wave + 4 * i) * 8 + (lane >> 3), piece = lane & 7;
+        const bf16_t *base = row < kRouteTokens ? x + (size_t)min(t0 + row, T - 1) * H
+                                                : wr + (size_t)min(row - kRouteTokens, NE - 1) * H;
+        src[i] = base + route_swz(row, piece) * 8;
+    }
+    // All workgroups read the same router rows, and rows are a power-of-two number of bytes apart, so one
+    // k chunk of every row sits on a single L2 channel: workgroups walking the chunks in the same order
+    // would queue on that channel.  Each starts at a different chunk instead (the sum over k does not
+    // depend on the order; the order is fixed per workgroup, so results stay reproducible).
+    const int nk = H / 64;
+    const int rot = (int)((blockIdx.x * 5u) % (unsigned)nk);
+    auto issue = [&](int chunk) {
+        unsigned char *slot = lds + (chunk % kRouteStages) * STAGE;
+        int kc = chunk + rot;
+        if (kc >= nk) kc -= nk;
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[i] + (size_t)kc * 64),
+                                             (__attribute__((address_space(3))) void *)(slot + (wave + 4 * i) * 1024), 16, 0, 0);
+    };
 
     f32x16 acc[NB];
 #pragma unroll
@@ -105,21 +186,27 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
 
-    for (int k0 = wave * 64; k0 < H; k0 += 4 * 64) {
-        bf16x8 xb[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) xb[s] = *reinterpret_cast<const bf16x8 *>(xrow + k0 + s * 8);
+    for (int c = 0; c < kRouteStages - 1; ++c)
+        if (c < nk) issue(c);
+    for (int it = 0; it < nk; ++it) {
+        if (it + kRouteStages - 2 < nk) route_wait_vmcnt<(kRouteStages - 2) * NL>();
+        else route_wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (it + kRouteStages - 1 < nk) issue(it + kRouteStages - 1);
+        const unsigned char *cur = lds + (it % kRouteStages) * STAGE;
+        // this wave's 16-wide step of the chunk: pieces 2*wave and 2*wave+1 of every row
+        const bf16x8 tb = *reinterpret_cast<const bf16x8 *>(cur + col * 128 + route_swz(col, 2 * wave + half) * 16);
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            bf16x8 wa[4];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) wa[s] = *reinterpret_cast<const bf16x8 *>(wrow[b] + k0 + s * 8);
-#pragma unroll
-            for (int s = 0; s < 4; ++s) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[s], xb[s], acc[b], 0, 0, 0);
+            const int row = kRouteTokens + b * 32 + col;
+            const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(cur + row * 128 + route_swz(row, 2 * wave + half) * 16);
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, tb, acc[b], 0, 0, 0);
         }
     }
+    __syncthreads();  // everyone is done with the ring: its memory now holds the logits
 
-    // acc[b][v]: expert 32b + 8(v/4) + 4*half + v%4, token col.  Add the four k-quarters in wave order.
+    // acc[b][v]: expert 32b + 8(v/4) + 4*half + v%4, token col.  Add the four partial sums in wave order.
     for (int w = 0; w < 4; ++w) {
         if (wave == w) {
 #pragma unroll
@@ -140,10 +227,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
         }
         __syncthreads();
     }
-    for (int tk = wave; tk < kRouteTokens; tk += 4) {
-        int t = t0 + tk;
-        if (t < T) select_token(&lg[tk * LD], NE, N, K, gate_norm, ids + (size_t)t * K, gates + (size_t)t * K);
-    }
+    select_block<4>(lg, LD, kRouteTokens, t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
 // fp32 router (plain FMA): a workgroup owns 8 tokens staged in LDS chunk by chunk; a wave walks the
@@ -194,10 +278,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_f32_kernel(const float *_
         for (int i = tid; i < kRouteF32Tokens * NE; i += kRouteThreads) lg[(i / NE) * LD + (i % NE)] += bias[i % NE];
         __syncthreads();
     }
-    for (int tk = wave; tk < kRouteF32Tokens; tk += 4) {
-        int t = t0 + tk;
-        if (t < T) select_token(&lg[tk * LD], NE, N, K, gate_norm, ids + (size_t)t * K, gates + (size_t)t * K);
-    }
+    select_block<2>(lg, LD, kRouteF32Tokens, t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
 template <int NB>
@@ -205,7 +286,13 @@ static void launch_route_bf16(const zeda_layer_desc *d, const void *x, const voi
                               float *gates, hipStream_t s)
 {
     dim3 grid(ceil_div(d->T, kRouteTokens));
-    route_bf16_kernel<NB><<<grid, kRouteThreads, 0, s>>>((const bf16_t *)x, (const bf16_t *)wr, bias, d->T, d->H, d->N,
+    constexpr int lds_bytes = kRouteStages * (kRouteTokens + 32 * NB) * 128;
+    static bool attr_set = false;  // per instantiation; idempotent, so a race between host threads is harmless
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void *)route_bf16_kernel<NB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        attr_set = true;
+    }
+    route_bf16_kernel<NB><<<grid, kRouteThreads, lds_bytes, s>>>((const bf16_t *)x, (const bf16_t *)wr, bias, d->T, d->H, d->N,
                                                          d->N + d->Z, d->K, d->gate_norm, ids, gates);
 }
 

@@ -1,0 +1,112 @@
+"""The C ABI without a GPU: the library loads, exports every symbol include/zeda.h declares, sizes its
+workspaces, and turns every invalid call into an error code before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_18643_amd import zeda
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "zeda.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(zeda_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = zeda.lib()
+    names = _declared_symbols()
+    assert {"zeda_route", "zeda_dispatch", "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(zeda.EXPORTS) == set(names)
+
+
+def test_status_strings():
+    assert zeda.status_string(0) == "ZEDA_OK"
+    assert zeda.status_string(-1) == "ZEDA_EINVAL"
+    assert zeda.status_string(-2) == "ZEDA_EUNSUPPORTED"
+    assert zeda.status_string(-3) == "ZEDA_EWORKSPACE"
+    assert zeda.status_string(-4) == "ZEDA_EHIP"
+
+
+def _desc(**kw):
+    base = dict(T=4096, H=2048, I=768, N=128, Z=32, K=8, dtype="bf16")
+    base.update(kw)
+    return zeda.make_desc(**base)
+
+
+def test_workspace_sizes():
+    d = _desc()
+    L = zeda.workspace_layout(d)
+    S = 4096 * 8
+    total = zeda.workspace_bytes(d)
+    assert total == L.total and total >= S * (4 + 4 + 4 + 4) + S * 768 * 2 + S * 2048 * 2
+    assert zeda.expert_ffn_workspace_bytes(d) >= S * 768 * 2 and zeda.expert_ffn_workspace_bytes(d) <= total
+    assert 0 < zeda.dispatch_workspace_bytes(d) <= total
+    offs = [L.topk_ids, L.topk_gates, L.expert_offsets, L.sorted_slot, L.slot_to_row, L.num_real, L.dispatch_ws, L.act,
+            L.y_slot, L.total]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+    # fp32 doubles the float buffers; Z = 0 and T = 0 are valid layers
+    assert zeda.workspace_bytes(_desc(dtype="f32")) > total
+    assert zeda.workspace_bytes(_desc(Z=0)) == total
+    assert zeda.workspace_bytes(_desc(T=0)) > 0
+
+
+@pytest.mark.parametrize("kw, code", [
+    (dict(T=-1), zeda.ZEDA_EINVAL), (dict(K=0), zeda.ZEDA_EINVAL), (dict(N=0), zeda.ZEDA_EINVAL),
+    (dict(Z=-1), zeda.ZEDA_EINVAL), (dict(N=4, Z=2, K=7), zeda.ZEDA_EINVAL), (dict(H=0), zeda.ZEDA_EINVAL),
+    (dict(K=17), zeda.ZEDA_EUNSUPPORTED), (dict(N=250, Z=7), zeda.ZEDA_EUNSUPPORTED),
+    (dict(H=2048 + 64), zeda.ZEDA_EUNSUPPORTED), (dict(I=768 + 32), zeda.ZEDA_EUNSUPPORTED),
+    (dict(dtype="f32", H=2050), zeda.ZEDA_EUNSUPPORTED), (dict(T=1 << 22), zeda.ZEDA_EUNSUPPORTED),
+])
+def test_descriptor_validation(kw, code):
+    d = _desc(**kw)
+    assert zeda.workspace_bytes(d) == 0
+    out = zeda.WsLayout()
+    assert zeda.lib().zeda_workspace_layout(ctypes.byref(d), ctypes.byref(out)) == code
+    # the compute entry points refuse the same descriptor before touching any pointer
+    p = ctypes.c_void_p(4096)
+    assert zeda.lib().zeda_route(ctypes.byref(d), p, p, None, p, p, None) == code
+    assert zeda.lib().zeda_moe_forward(ctypes.byref(d), p, p, None, p, p, p, p, None, p, 1 << 40, None) == code
+
+
+def test_bad_enum_values():
+    d = _desc()
+    d.dtype = 5
+    assert zeda.workspace_bytes(d) == 0
+    d = _desc()
+    d.gate_norm = 3
+    assert zeda.workspace_bytes(d) == 0
+
+
+def test_pointer_and_workspace_errors_return_before_any_launch():
+    lib = zeda.lib()
+    d = _desc()
+    ok = ctypes.c_void_p(1 << 20)       # aligned, never dereferenced: every call below fails validation first
+    odd = ctypes.c_void_p((1 << 20) + 8)
+    need = zeda.workspace_bytes(d)
+    dp = ctypes.byref(d)
+    assert lib.zeda_route(dp, None, ok, None, ok, ok, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_route(dp, odd, ok, None, ok, ok, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_route(dp, ok, ok, odd, ok, ok, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_dispatch(dp, ok, ok, ok, ok, ok, None, need, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_dispatch(dp, ok, ok, ok, ok, ok, ok, zeda.dispatch_workspace_bytes(d) - 1, None) == zeda.ZEDA_EWORKSPACE
+    assert lib.zeda_expert_ffn(dp, ok, ok, ok, ok, ok, ok, ok, None, ok, need, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_expert_ffn(dp, ok, ok, ok, ok, ok, ok, ok, ok, ok, zeda.expert_ffn_workspace_bytes(d) - 1, None) == zeda.ZEDA_EWORKSPACE
+    assert lib.zeda_combine(dp, ok, ok, ok, ok, None, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_combine(dp, ok, ok, ok, odd, ok, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_moe_forward(dp, ok, ok, None, ok, ok, ok, ok, None, ok, need - 1, None) == zeda.ZEDA_EWORKSPACE
+    assert lib.zeda_moe_forward(dp, ok, ok, None, ok, None, ok, ok, None, ok, need, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_moe_forward_events(dp, ok, ok, None, ok, ok, ok, ok, None, ok, need, None, None) == zeda.ZEDA_EINVAL
+
+
+def test_binding_raises_with_the_status_name():
+    d = _desc(K=0)
+    with pytest.raises(zeda.ZedaError) as ei:
+        zeda.workspace_layout(d)
+    assert ei.value.status == zeda.ZEDA_EINVAL and "ZEDA_EINVAL" in str(ei.value)
