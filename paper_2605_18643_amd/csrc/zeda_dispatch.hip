@@ -26,12 +26,29 @@ __global__ __launch_bounds__(kCountThreads) void dispatch_count_kernel(const int
     for (int e = tid; e < N; e += kCountThreads) hist[e] = 0;
     __syncthreads();
     const int base = blockIdx.x * kCountSlotsPerBlock;
-    for (int i = tid; i < kCountSlotsPerBlock; i += kCountThreads) {
-        int s = base + i;
-        if (s < S) {
-            int e = ids[s];
+    // 16 slots per thread, as four 16-byte loads that are all issued before any is used
+    constexpr int kVec = kCountSlotsPerBlock / kCountThreads / 4;
+    int4 v[kVec];
+#pragma unroll
+    for (int u = 0; u < kVec; ++u) {
+        const int s = base + (u * kCountThreads + tid) * 4;
+        if (s + 3 < S) v[u] = *reinterpret_cast<const int4 *>(ids + s);
+        else {
+            v[u].x = s + 0 < S ? ids[s + 0] : -2;
+            v[u].y = s + 1 < S ? ids[s + 1] : -2;
+            v[u].z = s + 2 < S ? ids[s + 2] : -2;
+            v[u].w = s + 3 < S ? ids[s + 3] : -2;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kVec; ++u) {
+        const int s = base + (u * kCountThreads + tid) * 4;
+        const int e4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = e4[q];
             if (e >= 0 && e < N) atomicAdd(&hist[e], 1);  // integer counts: the result does not depend on order
-            else slot_to_row[s] = -1;
+            else if (s + q < S) slot_to_row[s + q] = -1;
         }
     }
     __syncthreads();
@@ -53,7 +70,13 @@ __global__ __launch_bounds__(kPlaceThreads) void dispatch_place_kernel(const int
 
     if (tid < N) {
         int m = 0;
-        for (int b = 0; b < nblocks; ++b) m += block_hist[(size_t)b * N + tid];
+        for (int b0 = 0; b0 < nblocks; b0 += 8) {
+            int part[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) part[u] = b0 + u < nblocks ? block_hist[(size_t)(b0 + u) * N + tid] : 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) m += part[u];
+        }
         cnt[tid] = m;
     }
     __syncthreads();
@@ -125,12 +148,11 @@ __global__ __launch_bounds__(kPlaceThreads) void dispatch_place_kernel(const int
         for (int u = 0; u < kBatch; ++u) v[u] = (gb + u < g1) ? load4(gb + u) : make_int4(-1, -1, -1, -1);
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
-            my += (v[u].x == e) + (v[u].y == e) + (v[u].z == e) + (v[u].w == e);
+            my += __popcll(__ballot(v[u].x == e)) + __popcll(__ballot(v[u].y == e)) + __popcll(__ballot(v[u].z == e)) +
+                  __popcll(__ballot(v[u].w == e));
             keep[u] = v[u];
         }
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) my += __shfl_xor(my, off);
     if (lane == 0) wave_cnt[seg] = my;
     __syncthreads();
     int before = first_row;
@@ -144,21 +166,17 @@ __global__ __launch_bounds__(kPlaceThreads) void dispatch_place_kernel(const int
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             const bool hx = v[u].x == e, hy = v[u].y == e, hz = v[u].z == e, hw = v[u].w == e;
-            const int mine = hx + hy + hz + hw;
-            // matches in lower lanes of this group
-            int incl = mine;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                int o = __shfl_up(incl, off);
-                if (lane >= off) incl += o;
-            }
-            int r = before + incl - mine;
+            // matches in lower lanes of this group: ballots and bit counts, no cross-lane data movement
+            const unsigned long long bx = __ballot(hx), by = __ballot(hy), bz = __ballot(hz), bw = __ballot(hw);
+            const unsigned long long below = (1ull << lane) - 1ull;
+            int r = before + __popcll(bx & below) + __popcll(by & below) + __popcll(bz & below) + __popcll(bw & below);
+            const int group_total = __popcll(bx) + __popcll(by) + __popcll(bz) + __popcll(bw);
             const int s = ((gb + u) * 64 + lane) * 4;
             if (hx) { sorted_slot[r] = s + 0; slot_to_row[s + 0] = r; ++r; }
             if (hy) { sorted_slot[r] = s + 1; slot_to_row[s + 1] = r; ++r; }
             if (hz) { sorted_slot[r] = s + 2; slot_to_row[s + 2] = r; ++r; }
             if (hw) { sorted_slot[r] = s + 3; slot_to_row[s + 3] = r; ++r; }
-            before += __shfl(incl, 63);
+            before += group_total;
         }
     }
 }

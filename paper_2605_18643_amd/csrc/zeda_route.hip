@@ -8,19 +8,48 @@ namespace zeda {
 constexpr int kRouteTokens = 32;  // tokens per workgroup of the bf16 kernel (one MFMA column block)
 constexpr int kRouteThreads = 256;
 
+// Wave-wide reductions on the VALU data-parallel-primitive path (no LDS traffic): an inclusive scan inside
+// each row of 16 lanes with row_shr 1, 2, 4, 8 leaves the row result in its last lane; the four row results
+// are then combined in a fixed order.  Every lane returns the same value.
+template <int CTRL>
+__device__ __forceinline__ float dpp_row_shr(float old, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float rows_to_all(float v, bool is_max)
+{
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 15));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 47));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+    return is_max ? fmaxf(fmaxf(r0, r1), fmaxf(r2, r3)) : ((r0 + r1) + (r2 + r3));
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+    v = fmaxf(v, dpp_row_shr<0x111>(v, v));  // lanes without a source keep their own value
+    v = fmaxf(v, dpp_row_shr<0x112>(v, v));
+    v = fmaxf(v, dpp_row_shr<0x114>(v, v));
+    v = fmaxf(v, dpp_row_shr<0x118>(v, v));
+    return rows_to_all(v, true);
+}
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-    return v;
+    v += dpp_row_shr<0x111>(0.f, v);  // lanes without a source add zero
+    v += dpp_row_shr<0x112>(0.f, v);
+    v += dpp_row_shr<0x114>(0.f, v);
+    v += dpp_row_shr<0x118>(0.f, v);
+    return rows_to_all(v, false);
 }
 
 // Selection and gates for NT tokens at once (tokens base, base+4, ... of the workgroup's block, whose
-// fp32 logits are rows of lg in LDS), executed by one wave.  The c-th candidate of a lane is expert lane + 64*c.  The NT reduction
-// chains are independent and written side by side so that their cross-lane exchanges overlap.
-template <int NT>
-__device__ __forceinline__ void select_tokens(const float *lg, int LD, int base, int ntok, int t0, int T, int NE, int N,
-                                              int K, int gate_norm, int32_t *__restrict__ ids, float *__restrict__ gates)
+// fp32 logits are rows of lg in LDS), executed by one wave.  The c-th candidate of a lane is expert
+// lane + 64*c.  One round: the wave maximum, then ballots of the candidates equal to it; the winner is the
+// lowest set bit of the first non-empty ballot, i.e. the lowest expert index among equal logits.  The NT
+// chains are independent and written side by side so that they overlap.
+template <int NT, int NP>
+__device__ __forceinline__ void select_tokens(const float *lg, int LD, int pstride, const float *__restrict__ bias, int base,
+                                              int ntok, int t0, int T, int NE, int N, int K, int gate_norm,
+                                              int32_t *__restrict__ ids, float *__restrict__ gates)
 {
     const int lane = threadIdx.x & 63;
     bool ok[NT];
@@ -33,90 +62,75 @@ __device__ __forceinline__ void select_tokens(const float *lg, int LD, int base,
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             int e = lane + 64 * c;
-            cand[i][c] = (ok[i] && e < NE) ? lg[(base + 4 * i) * LD + e] : -INFINITY;
+            float v = -INFINITY;
+            if (ok[i] && e < NE) {
+                // the NP partial sums over slices of the hidden dimension, added in a fixed order, then the bias
+                v = lg[(base + 4 * i) * LD + e];
+#pragma unroll
+                for (int q = 1; q < NP; ++q) v += lg[q * pstride + (base + 4 * i) * LD + e];
+                if (bias) v += bias[e];
+            }
+            cand[i][c] = v;
         }
-        all_max[i] = fmaxf(fmaxf(cand[i][0], cand[i][1]), fmaxf(cand[i][2], cand[i][3]));
         my_id[i] = 0;
         my_logit[i] = -INFINITY;
         all_sum[i] = 0.f;
     }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1)
-#pragma unroll
-        for (int i = 0; i < NT; ++i) all_max[i] = fmaxf(all_max[i], __shfl_xor(all_max[i], off));
+    for (int i = 0; i < NT; ++i)
+        all_max[i] = wave_max(fmaxf(fmaxf(cand[i][0], cand[i][1]), fmaxf(cand[i][2], cand[i][3])));
     if (gate_norm == ZEDA_GATE_SOFTMAX) {
 #pragma unroll
-        for (int i = 0; i < NT; ++i)
+        for (int i = 0; i < NT; ++i) {
+            float sacc = 0.f;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) all_sum[i] += (lane + 64 * c < NE) ? expf(cand[i][c] - all_max[i]) : 0.f;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1)
-#pragma unroll
-            for (int i = 0; i < NT; ++i) all_sum[i] += __shfl_xor(all_sum[i], off);
+            for (int c = 0; c < 4; ++c) sacc += (lane + 64 * c < NE) ? expf(cand[i][c] - all_max[i]) : 0.f;
+            all_sum[i] = wave_sum(sacc);
+        }
     }
     for (int j = 0; j < K; ++j) {
-        float bv[NT];
-        int bi[NT];
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            bv[i] = cand[i][0];
-            bi[i] = lane;
+            const float m = wave_max(fmaxf(fmaxf(cand[i][0], cand[i][1]), fmaxf(cand[i][2], cand[i][3])));
+            int win = -1;
 #pragma unroll
-            for (int c = 1; c < 4; ++c)
-                if (cand[i][c] > bv[i]) { bv[i] = cand[i][c]; bi[i] = lane + 64 * c; }
-        }
-        // (value, index) butterfly: every lane ends with the maximum value, ties to the lower index
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1)
-#pragma unroll
-            for (int i = 0; i < NT; ++i) {
-                float ov = __shfl_xor(bv[i], off);
-                int oi = __shfl_xor(bi[i], off);
-                if (ov > bv[i] || (ov == bv[i] && oi < bi[i])) { bv[i] = ov; bi[i] = oi; }
+            for (int c = 3; c >= 0; --c) {
+                const unsigned long long hit = __ballot(cand[i][c] == m);
+                if (hit) win = 64 * c + (__ffsll((long long)hit) - 1);  // descending c: the lowest index survives
             }
 #pragma unroll
-        for (int i = 0; i < NT; ++i) {
-            if ((bi[i] & 63) == lane) {
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    if ((bi[i] >> 6) == c) cand[i][c] = -INFINITY;
-            }
-            if (lane == j) { my_id[i] = bi[i]; my_logit[i] = bv[i]; }
+            for (int c = 0; c < 4; ++c)
+                if (win == lane + 64 * c) cand[i][c] = -INFINITY;
+            if (lane == j) { my_id[i] = win; my_logit[i] = m; }
         }
     }
     // lanes 0..K-1 hold the slots in descending-logit order
     const bool slot = lane < K;
-    float ex[NT], denom[NT];
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
-        ex[i] = slot ? expf(my_logit[i] - all_max[i]) : 0.f;
-        denom[i] = gate_norm == ZEDA_GATE_TOPK_NORM ? ex[i] : ((slot && my_id[i] < N) ? ex[i] : 0.f);
-    }
-    if (gate_norm != ZEDA_GATE_SOFTMAX) {
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1)
-#pragma unroll
-            for (int i = 0; i < NT; ++i) denom[i] += __shfl_xor(denom[i], off);
-    }
-#pragma unroll
-    for (int i = 0; i < NT; ++i) {
-        const float dn = gate_norm == ZEDA_GATE_SOFTMAX ? all_sum[i] : denom[i];
+        const float ex = slot ? expf(my_logit[i] - all_max[i]) : 0.f;
+        float dn;
+        if (gate_norm == ZEDA_GATE_SOFTMAX) dn = all_sum[i];
+        else if (gate_norm == ZEDA_GATE_TOPK_NORM) dn = wave_sum(ex);
+        else dn = wave_sum((slot && my_id[i] < N) ? ex : 0.f);
         if (slot && ok[i]) {
             const size_t o = (size_t)(t0 + base + 4 * i) * K + lane;
             ids[o] = my_id[i];
-            gates[o] = dn > 0.f ? ex[i] / dn : 0.f;
+            gates[o] = dn > 0.f ? ex / dn : 0.f;
         }
     }
 }
 
-// The tokens tk = wave, wave + 4, ... < ntok of a workgroup, NT at a time.
-template <int NT>
-__device__ __forceinline__ void select_block(const float *lg, int LD, int ntok, int t0, int T, int NE, int N, int K,
-                                             int gate_norm, int32_t *__restrict__ ids, float *__restrict__ gates)
+// The tokens tk = wave, wave + 4, ... < ntok of a workgroup, NT at a time.  lg holds NP partial logit
+// tables pstride floats apart.
+template <int NT, int NP>
+__device__ __forceinline__ void select_block(const float *lg, int LD, int pstride, const float *__restrict__ bias, int ntok,
+                                             int t0, int T, int NE, int N, int K, int gate_norm, int32_t *__restrict__ ids,
+                                             float *__restrict__ gates)
 {
     const int wave = threadIdx.x >> 6;
     for (int base = wave; base < ntok; base += 4 * NT)
-        select_tokens<NT>(lg, LD, base, ntok, t0, T, NE, N, K, gate_norm, ids, gates);
+        select_tokens<NT, NP>(lg, LD, pstride, bias, base, ntok, t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
 // bf16 router.  A workgroup owns kRouteTokens tokens and all NE experts (NB MFMA row blocks of 32; tokens
@@ -124,8 +138,9 @@ __device__ __forceinline__ void select_block(const float *lg, int LD, int ntok, 
 // k chunks with global->LDS loads, 128-byte rows whose 16-byte pieces are XOR-permuted by the row index
 // (applied on the global address) so that fragment reads spread over the banks; a counted s_waitcnt and
 // one s_barrier per chunk order the ring.  The four waves split the four 16-wide MFMA steps of every
-// chunk, so each holds a partial sum over a quarter of the hidden dimension; the partial sums are added
-// in LDS in wave order (a fixed order: the logits are reproducible), then each wave selects for 8 tokens.
+// chunk, so each holds a partial sum over a quarter of the hidden dimension; each stores it in an LDS table
+// of its own and the selection adds the four tables in wave order (a fixed order: the logits are
+// reproducible); each wave selects for 8 tokens, four at a time.
 constexpr int kRouteStages = 4;
 
 __device__ __forceinline__ int route_swz(int row, int piece) { return piece ^ ((row >> 1) & 7); }
@@ -148,7 +163,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
     constexpr int STAGE = ROWS * 128;
     constexpr int NL = 1 + NB;                    // wave load instructions (8 rows each) per chunk and wave
     static_assert(kRouteTokens == 32 && kRouteThreads == 256, "one token block, four waves");
-    static_assert(kRouteTokens * LD * 4 <= kRouteStages * STAGE, "the logits reuse the ring");
+    static_assert(4 * kRouteTokens * LD * 4 <= kRouteStages * STAGE, "the four partial logit tables reuse the ring");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     float *lg = reinterpret_cast<float *>(lds);
 
@@ -206,28 +221,15 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
     }
     __syncthreads();  // everyone is done with the ring: its memory now holds the logits
 
-    // acc[b][v]: expert 32b + 8(v/4) + 4*half + v%4, token col.  Add the four partial sums in wave order.
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
+    // acc[b][v]: expert 32b + 8(v/4) + 4*half + v%4, token col.  Every wave stores its partial sums in a table
+    // of its own; the selection adds the four tables in wave order (a fixed order) when it reads them.
+    float *mine = lg + wave * (kRouteTokens * LD);
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int e = b * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                    float *p = &lg[col * LD + e];
-                    *p = (w == 0) ? acc[b][v] : *p + acc[b][v];
-                }
-        }
-        __syncthreads();
-    }
-    if (bias) {
-        for (int i = tid; i < kRouteTokens * NE; i += kRouteThreads) {
-            int tk = i / NE, e = i - tk * NE;
-            lg[tk * LD + e] += bias[e];
-        }
-        __syncthreads();
-    }
-    select_block<4>(lg, LD, kRouteTokens, t0, T, NE, N, K, gate_norm, ids, gates);
+        for (int v = 0; v < 16; ++v) mine[col * LD + b * 32 + 8 * (v >> 2) + 4 * half + (v & 3)] = acc[b][v];
+    __syncthreads();
+    select_block<4, 4>(lg, LD, kRouteTokens * LD, bias, kRouteTokens, t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
 // fp32 router (plain FMA): a workgroup owns 8 tokens staged in LDS chunk by chunk; a wave walks the
@@ -274,11 +276,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_f32_kernel(const float *_
         }
     }
     __syncthreads();
-    if (bias) {
-        for (int i = tid; i < kRouteF32Tokens * NE; i += kRouteThreads) lg[(i / NE) * LD + (i % NE)] += bias[i % NE];
-        __syncthreads();
-    }
-    select_block<2>(lg, LD, kRouteF32Tokens, t0, T, NE, N, K, gate_norm, ids, gates);
+    select_block<2, 1>(lg, LD, 0, bias, kRouteF32Tokens, t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
 template <int NB>
