@@ -67,12 +67,48 @@ def run_layer(w: synth.Workload, L, steps: int, warmup: int):
             "max_rows": int(np.diff(off).max()), "out": out}
 
 
+def stack_bench(a) -> int:
+    """BASELINE config 5: time the chained stack at Z=32 and at Z=0 (same weights, router restricted to the
+    normal experts); one step = one pass of all layers over T=8192 tokens."""
+    from paper_2605_18643_amd.stack import MoeStack
+
+    w = synth.CONFIGS["c5_stack_layer"]
+    res = {}
+    x0 = synth.draw_tokens(w, "cuda")
+    for name, static in (("z32", False), ("z0", True)):
+        st = MoeStack(w, a.layers, static=static)
+        x = x0.clone()
+        for _ in range(max(1, a.warmup // 2)):
+            st.forward(x.copy_(x0))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            st.forward(x.copy_(x0))
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / a.steps
+        res[name] = {"ms_per_pass": dt * 1e3, "real_slots": int(st.num_real.sum().item())}
+        del st
+        torch.cuda.empty_cache()
+    out = {"metric": "48-layer MoE stack tokens/s (Qwen3-30B-A3B layer shape, T=8192, ~50% zero slots)",
+           "value": w.T / (res["z32"]["ms_per_pass"] * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
+           "warmup": a.warmup, "ms_per_step": res["z32"]["ms_per_pass"], "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+           "config": {"workload": "c5_stack", "layers": a.layers, "T": w.T, "H": w.H, "I": w.I, "N": w.N, "Z": w.Z, "K": w.K},
+           "z32": res["z32"], "z0": res["z0"],
+           "stack_speedup_vs_z0": res["z0"]["ms_per_pass"] / res["z32"]["ms_per_pass"],
+           "expert_flop_reduction": 1.0 - res["z32"]["real_slots"] / max(1, res["z0"]["real_slots"])}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2_qwen_prefill", choices=sorted(synth.CONFIGS))
+    ap.add_argument("--workload", default="c2_qwen_prefill", choices=sorted(synth.CONFIGS) + ["c5_stack"],
+                    help="c5_stack: the 48-layer chain (RMSNorm + residual, no attention) with and without zero experts")
+    ap.add_argument("--layers", type=int, default=48)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-z0", action="store_true")
     a = ap.parse_args()
@@ -84,6 +120,8 @@ def main() -> int:
         print("bench.py needs a GPU (the HIP library has no CPU fallback)", file=sys.stderr)
         return 2
     zeda.lib()
+    if a.workload == "c5_stack":
+        return stack_bench(a)
 
     w = synth.CONFIGS[a.workload]
     L = synth.make_layer(w, "cuda")

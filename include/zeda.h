@@ -139,6 +139,15 @@ typedef struct {
 } zeda_ws_layout;
 int zeda_workspace_layout(const zeda_layer_desc *desc, zeda_ws_layout *layout /* host */);
 
+/* Glue of the layer-stack workload x <- x + MoE_l(RMSNorm(x)) (no attention).  Not part of the paper's layer
+ * (Appendix D leaves norms and residuals out of its model); used to chain 48 layers with and without zero
+ * experts.  x, out, y: [T,H] of `dtype` (zeda_dtype); arithmetic in fp32.
+ *   zeda_rmsnorm:       out[t,:] = x[t,:] / sqrt(mean(x[t,:]^2) + eps) * gamma   (gamma[H] may be NULL = 1)
+ *   zeda_residual_add:  x += y  (in place)
+ * ZEDA_EINVAL on NULL pointers, bad dtype, T < 0, H < 1, eps < 0. */
+int zeda_rmsnorm(int32_t T, int32_t H, int32_t dtype, const void *x, const void *gamma, float eps, void *out, void *stream);
+int zeda_residual_add(int32_t T, int32_t H, int32_t dtype, void *x, const void *y, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

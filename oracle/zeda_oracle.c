@@ -236,6 +236,18 @@ void oracle_combine(const double *y_rows, const int32_t *ids, const double *gate
     }
 }
 
+/* Pre-norm of the layer-stack workload (not part of the paper's layer, whose model leaves norms out, Appendix D):
+ * out[t,:] = x[t,:] / sqrt(mean_h x[t,h]^2 + eps) * gamma[h]   (gamma may be NULL = 1). */
+void oracle_rmsnorm(const double *x, const double *gamma, int T, int H, double eps, double *out)
+{
+    for (int t = 0; t < T; ++t) {
+        double ss = 0.0;
+        for (int h = 0; h < H; ++h) ss += x[(size_t)t * H + h] * x[(size_t)t * H + h];
+        const double scale = 1.0 / sqrt(ss / H + eps);
+        for (int h = 0; h < H; ++h) out[(size_t)t * H + h] = x[(size_t)t * H + h] * scale * (gamma ? gamma[h] : 1.0);
+    }
+}
+
 /* Appendix D, Eq. 9 / Eq. 10: MoE-branch FLOPs for n tokens (r_ze = 0 and nz = 0 give the original model). */
 double oracle_moe_flops(double n, double H, double He, double N, double NZ, double K, double r_ze)
 {

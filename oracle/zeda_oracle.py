@@ -143,6 +143,16 @@ def combine(y_rows, ids, gates, slot_to_row, N: int) -> np.ndarray:
     return out
 
 
+def rmsnorm(x, gamma=None, eps: float = 1e-6) -> np.ndarray:
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    T, H = x.shape
+    g = None if gamma is None else np.ascontiguousarray(gamma, dtype=np.float64)
+    out = np.empty_like(x)
+    lib.oracle_rmsnorm(_p(x), _p(g), T, H, ctypes.c_double(eps), _p(out))
+    return out
+
+
 def moe_flops(n, H, He, N, NZ, K, r_ze) -> float:
     return float(_load().oracle_moe_flops(n, H, He, N, NZ, K, r_ze))
 

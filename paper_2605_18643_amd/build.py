@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIB_DIR, "libzeda.so")
-SOURCES = ["zeda_api.hip", "zeda_route.hip", "zeda_dispatch.hip", "zeda_ffn.hip", "zeda_combine.hip"]
+SOURCES = ["zeda_api.hip", "zeda_route.hip", "zeda_dispatch.hip", "zeda_ffn.hip", "zeda_combine.hip", "zeda_stack.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed fp32 instructions are switched off for all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

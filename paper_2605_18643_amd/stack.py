@@ -1,0 +1,44 @@
+"""The layer-stack workload: L MoE layers chained as x <- x + MoE_l(RMSNorm(x)), no attention (BASELINE
+config 5).  This file only owns buffers and the order of the C-ABI calls; every step runs in the HIP library."""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import torch
+
+from . import synth, zeda
+
+EPS = 1e-6
+
+
+class MoeStack:
+    """Per-layer weights drawn by synth (layer l uses seed + l) and the scratch for one pass."""
+
+    def __init__(self, w: synth.Workload, layers: int, device="cuda", static: bool = False):
+        self.w = w if not static else w.with_(Z=0, recipe="plain")
+        self.layers = layers
+        self.weights: List[Dict[str, Optional[torch.Tensor]]] = []
+        for l in range(layers):
+            wr, bias = synth.draw_router(w, device, l)
+            wg, wu, wd = synth.draw_experts(w, device, l)
+            if static:  # the static top-K layer: router restricted to the normal experts, no bias
+                wr, bias = wr[: w.N].contiguous(), None
+            self.weights.append({"w_router": wr, "router_bias": bias, "w_gate": wg, "w_up": wu, "w_down": wd})
+        ww = self.w
+        self.desc = zeda.make_desc(ww.T, ww.H, ww.I, ww.N, ww.Z, ww.K, ww.dtype)
+        self.ws = torch.empty(zeda.workspace_bytes(self.desc), dtype=torch.uint8, device=device)
+        self.xn = torch.empty((ww.T, ww.H), dtype=ww.torch_dtype, device=device)
+        self.y = torch.empty((ww.T, ww.H), dtype=ww.torch_dtype, device=device)
+        self.num_real = torch.zeros(layers, dtype=torch.int32, device=device)
+
+    def forward(self, x: torch.Tensor, hook=None) -> torch.Tensor:
+        """Runs the chain in place on x (the residual stream) and returns it.  hook(l, stack) is called after
+        layer l's MoE output is in self.y and before the residual add (the stream is not synchronised)."""
+        for l, p in enumerate(self.weights):
+            zeda.zeda_rmsnorm(x, None, EPS, self.xn)
+            zeda.zeda_moe_forward(self.desc, self.xn, p["w_router"], p["router_bias"], p["w_gate"], p["w_up"], p["w_down"],
+                                  self.y, self.num_real[l: l + 1], self.ws)
+            if hook is not None:
+                hook(l, self)
+            zeda.zeda_residual_add(x, self.y)
+        return x

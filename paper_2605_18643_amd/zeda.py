@@ -21,7 +21,8 @@ STAGES = ("route", "dispatch", "gateup", "down", "combine")
 
 EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_dispatch_workspace_bytes",
            "zeda_expert_ffn_workspace_bytes", "zeda_workspace_layout", "zeda_route", "zeda_dispatch",
-           "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events")
+           "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events", "zeda_rmsnorm",
+           "zeda_residual_add")
 
 
 class LayerDesc(ctypes.Structure):
@@ -70,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.zeda_moe_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.zeda_moe_forward_events.restype = i32
         L.zeda_moe_forward_events.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(vp)]
+        L.zeda_rmsnorm.restype = i32
+        L.zeda_rmsnorm.argtypes = [i32, i32, i32, vp, vp, ctypes.c_float, vp, vp]
+        L.zeda_residual_add.restype = i32
+        L.zeda_residual_add.argtypes = [i32, i32, i32, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -157,6 +162,21 @@ def zeda_moe_forward_events(desc, x, w_router, router_bias, w_gate, w_up, w_down
                                          _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(num_real_out),
                                          _ptr(ws), ws.numel() * ws.element_size(), _stream(stream), arr),
            "zeda_moe_forward_events")
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    return ZEDA_BF16 if t.dtype == torch.bfloat16 else ZEDA_F32
+
+
+def zeda_rmsnorm(x, gamma, eps: float, out, stream=None) -> None:
+    T, H = x.shape
+    _check(lib().zeda_rmsnorm(T, H, _dtype_code(x), _ptr(x), _ptr(gamma), float(eps), _ptr(out), _stream(stream)),
+           "zeda_rmsnorm")
+
+
+def zeda_residual_add(x, y, stream=None) -> None:
+    T, H = x.shape
+    _check(lib().zeda_residual_add(T, H, _dtype_code(x), _ptr(x), _ptr(y), _stream(stream)), "zeda_residual_add")
 
 
 def ws_views(desc: LayerDesc, ws: torch.Tensor):
