@@ -86,28 +86,42 @@ __global__ __launch_bounds__(kF32Threads) void ffn_f32_down_kernel(const float *
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
-//              G FB WF NSTAGE
-typedef TileCfg<4, 2, 4, 2> CfgPrefill;  // 256 tokens x 256 weight rows, 8 waves, 128 KiB of LDS
-typedef TileCfg<4, 2, 2, 2> CfgNarrow;   // 256 tokens x 128 weight rows, 4 waves: any H % 128 == 0, I % 64 == 0
-typedef TileCfg<1, 2, 2, 3> CfgDecode;   // 64 tokens x 128 weight rows, 4 waves, three chunks deep, two per CU
+//              G FB WF NSTAGE KC
+typedef TileCfg<4, 2, 4, 2, 64> CfgPrefill;  // 256 tokens x 256 weight rows, 8 waves, one workgroup per CU
+typedef TileCfg<4, 2, 2, 2, 64> CfgNarrow;   // 256 tokens x 128 weight rows, 4 waves: any H % 128 == 0, I % 64 == 0
+typedef TileCfg<1, 2, 2, 4, 32> CfgDecode;   // 64 tokens x 128 weight rows, 4 waves, four chunks deep, two per CU
 
-template <class C, bool GATEUP, typename OutT>
+// Persistent grid: as many workgroups as the device holds at once, rounded down to a multiple of 8 so that
+// every XCD gets the same number (the kernel reads the count from gridDim).
+template <class C, bool GATEUP>
+static int resident_grid()
+{
+    static int grid = 0;  // per instantiation; idempotent, so a race between host threads is harmless
+    if (grid == 0) {
+        auto kern = ffn_bf16_kernel<C, GATEUP>;
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kern, C::THREADS, C::LDS_BYTES) != hipSuccess)
+            return 0;
+        const int g = cus * (per_cu > 0 ? per_cu : 1) / 8 * 8;
+        grid = g > 0 ? g : 8;
+    }
+    return grid;
+}
+
+template <class C, bool GATEUP>
 static int launch_tile_kernel(const zeda_layer_desc *d, const void *tok, const void *w0, const void *w1,
                               const int32_t *offsets, const int32_t *sorted_slot, void *out, hipStream_t s)
 {
-    auto kern = ffn_bf16_kernel<C, GATEUP, OutT>;
-    static bool attr_set = false;  // per instantiation; idempotent, so a race between host threads is harmless
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) !=
-            hipSuccess)
-            return ZEDA_EHIP;
-        attr_set = true;
-    }
+    const int grid = resident_grid<C, GATEUP>();
+    if (grid == 0) return ZEDA_EHIP;
     const int Kdim = GATEUP ? d->H : d->I, Fdim = GATEUP ? d->I : d->H;
     const int n_ftiles = GATEUP ? Fdim / (C::BF / 2) : Fdim / C::BF;
-    const int grid = ffn_grid<C>(d->T, d->K, d->N, n_ftiles);
-    kern<<<grid, C::THREADS, C::LDS_BYTES, s>>>((const bf16_t *)tok, (const bf16_t *)w0, (const bf16_t *)w1, offsets,
-                                               sorted_slot, (OutT *)out, d->N, d->K, Kdim, Fdim, n_ftiles, d->T);
+    ffn_bf16_kernel<C, GATEUP><<<grid, C::THREADS, C::LDS_BYTES, s>>>((const bf16_t *)tok, (const bf16_t *)w0,
+                                                                     (const bf16_t *)w1, offsets, sorted_slot,
+                                                                     (bf16_t *)out, d->N, d->K, Kdim, Fdim, n_ftiles, d->T);
     return last_launch_status();
 }
 
@@ -124,10 +138,10 @@ static int launch_bf16(const zeda_layer_desc *d, const void *tok, const void *w0
 {
     // an expert never has more rows than there are tokens: small batches take the short token tile
     if (d->T <= CfgDecode::BT && cfg_fits<CfgDecode>(d))
-        return launch_tile_kernel<CfgDecode, GATEUP, bf16_t>(d, tok, w0, w1, offsets, sorted_slot, out, s);
+        return launch_tile_kernel<CfgDecode, GATEUP>(d, tok, w0, w1, offsets, sorted_slot, out, s);
     if (cfg_fits<CfgPrefill>(d))
-        return launch_tile_kernel<CfgPrefill, GATEUP, bf16_t>(d, tok, w0, w1, offsets, sorted_slot, out, s);
-    return launch_tile_kernel<CfgNarrow, GATEUP, bf16_t>(d, tok, w0, w1, offsets, sorted_slot, out, s);
+        return launch_tile_kernel<CfgPrefill, GATEUP>(d, tok, w0, w1, offsets, sorted_slot, out, s);
+    return launch_tile_kernel<CfgNarrow, GATEUP>(d, tok, w0, w1, offsets, sorted_slot, out, s);
 }
 
 int launch_gateup(const zeda_layer_desc *d, const void *x, const void *wg, const void *wu, const int32_t *offsets,

@@ -1,313 +1,503 @@
 // Grouped bf16 GEMM tile kernel of the expert FFN (Appendix D, Eq. 10: gate, up and down projections of
 // the real slots only).  See zeda_ffn.hip for how the two GEMMs use it.
 //
-// A workgroup owns (expert, token tile, feature tile).  Weight rows are the MFMA "A" operand (output
-// rows), tokens the "B" operand (output columns): a lane then holds 4 consecutive output features of one
-// token per register quad and stores them as one 8- or 16-byte word.
+// A work item is (expert, token tile, feature tile).  Weight rows are the MFMA "A" operand (output rows),
+// tokens the "B" operand (output columns), all in 32x32 blocks with 16-wide k steps.
 //
-// Data movement.  Both tiles stream through an NSTAGE-deep ring in LDS in 64-wide k chunks, fetched with
-// global->LDS loads (no staging registers): one wave instruction moves 64 pieces of 16 bytes to 1 KiB of
-// consecutive LDS, i.e. 8 rows of 128 bytes, so lane l fetches the piece that belongs at position l of
-// that KiB.  The 8 pieces of a row are XOR-permuted by the row index so that the 16 rows a fragment read
-// touches per phase fall on distinct banks; the permutation is applied on the global address, which
-// costs nothing.  NSTAGE-1 chunks are in flight while one is multiplied; a counted s_waitcnt and one
-// s_barrier per chunk order the ring (the wait covers this thread's own loads, the barrier extends it to
-// the workgroup and also guarantees that everyone has left the slot about to be refilled).
+// Persistent workgroups.  The grid is one workgroup per CU slot; workgroup ids go round-robin over the 8
+// XCDs, so each XCD takes a contiguous eighth of the work items that exist (their number is only known on
+// the device, from expert_offsets) and its workgroups walk that eighth with a stride.  A workgroup first
+// looks up its items (up to MAXQ at a time) and writes, per item, the tile location and the source row of
+// every tile row to LDS; after that the main stream touches global memory only through global->LDS loads
+// and the output stores.
 //
-// With about half of the slots on zero experts an expert sees few rows and the GEMM is bound by streaming
-// its weights from HBM, so the tile is shaped around that: all rows of an expert up to 64*G form one
-// token tile (the expert's weights then stream exactly once), only the 64-row groups that hold rows are
-// fetched and multiplied (the group count is a template parameter of the main loop, so it has no
-// branches), and the two wave rows take alternate 32-row blocks so that both always have equal work.
+// One continuous stream of chunks.  Both operand tiles move through an NSTAGE-deep ring in LDS in KC-wide
+// k chunks, fetched with global->LDS loads (no staging registers): one wave instruction moves 64 pieces of
+// 16 bytes to 1 KiB of consecutive LDS, so lane l fetches the piece that belongs at position l of that
+// KiB.  The pieces of a row are XOR-permuted by the row index so that the 16 rows a fragment read touches
+// per phase fall on distinct banks; the permutation is applied on the global address.  The chunks of all
+// items of a workgroup form ONE sequence: while the last chunks of an item are multiplied and its result
+// is written, the first chunks of the next item are already in flight, so HBM never sees the pipeline
+// drain between tiles.  Per chunk there is one counted s_waitcnt (this wave's own loads of that chunk)
+// and one s_barrier (everybody's loads have landed, and everybody has left the slot that is refilled
+// next).  The refill is issued a few instructions at a time between the MFMAs that follow the barrier,
+// so that the texture path never sees all waves issue at once; fragments are double-buffered in
+// registers and read one k step ahead.
 //
-// There is no host-side work list: every workgroup derives its tile from expert_offsets with a wave
-// scan, so the grid is sized for the worst case and surplus workgroups return at once; experts with no
-// rows get no tile at all.  Each XCD walks a contiguous eighth of the tiles that exist (see locate_tile).
+// Only the 64-row groups of a token tile that hold rows are fetched and multiplied (their number is a
+// template parameter of the tile body, so the MFMA loop has no branches), and the two wave rows take
+// alternate 32-row blocks so that both always have equal work.  Results leave through a small per-wave
+// LDS buffer that turns the MFMA layout (a lane owns 4 features of one token) into 64-byte row segments.
 #pragma once
 #include "zeda_internal.h"
 
 namespace zeda {
 
-template <int G_, int FB_, int WF_, int NSTAGE_>
+template <int G_, int FB_, int WF_, int NSTAGE_, int KC_>
 struct TileCfg {
-    static constexpr int G = G_, FB = FB_, WF = WF_, NSTAGE = NSTAGE_;
+    static constexpr int G = G_, FB = FB_, WF = WF_, NSTAGE = NSTAGE_, KC = KC_;
     static constexpr int WT = 2;                  // wave rows: wave row wt owns token blocks wt, wt+2, ...
     static constexpr int BT = 64 * G;             // tokens per tile
     static constexpr int BF = 32 * FB * WF;       // weight rows per tile (gate and up rows both count)
     static constexpr int NW = WT * WF;            // waves
     static constexpr int THREADS = 64 * NW;
-    static constexpr int STAGE = (BT + BF) * 128;  // bytes per ring slot: rows of 64 bf16
-    static constexpr int LDS_BYTES = NSTAGE * STAGE;
-    // wave load instructions (8 rows each) per chunk and wave when g 64-row groups are live
-    static constexpr int nl(int g) { return (8 * g + BF / 8) / NW; }
-    static_assert((BF / 8) % NW == 0 && 8 % NW == 0, "loads must divide evenly over the waves for every group count");
-    static_assert(NSTAGE >= 2 && (NSTAGE - 1) * nl(G) <= 63, "vmcnt is a 6-bit counter");
+    static constexpr int ROWB = 2 * KC;           // bytes of one row of a chunk
+    static constexpr int PPR = ROWB / 16;         // 16-byte pieces per row
+    static constexpr int RPI = 64 / PPR;          // rows covered by one wave load instruction
+    static constexpr int KS = KC / 16;            // MFMA k steps per chunk
+    static constexpr int STAGE = (BT + BF) * ROWB;
+    static constexpr int RING = NSTAGE * STAGE;
+    static constexpr int NWI = BF / RPI;          // load instructions per chunk that fetch weight rows
+    static constexpr int nti(int g) { return 64 * g / RPI; }  // ... that fetch the rows of g live token groups
+    static constexpr int NLMAX = (nti(G) + NWI + NW - 1) / NW;  // most load instructions per wave and chunk
+    static constexpr int MAXQ = 8;                // items looked up at a time
+    static constexpr int TOK_OFF = RING;                     // int32 [MAXQ][BT]: source row of every tile row
+    static constexpr int LOC_OFF = TOK_OFF + MAXQ * BT * 4;  // int4  [MAXQ]: expert, row0, rows, feature tile
+    static constexpr int STG_OFF = LOC_OFF + MAXQ * 16;      // 2 KiB per wave: output transposition
+    static constexpr int LDS_BYTES = STG_OFF + NW * 2048;
+    static_assert(KC == 32 || KC == 64, "rows of 64 or 128 bytes");
+    static_assert(NSTAGE >= 2 && (NSTAGE - 1) * NLMAX <= 63, "vmcnt is a 6-bit counter");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS is 160 KiB per CU");
 };
 
-// position of logical piece p of row r inside its 128-byte LDS row (an involution in p)
-__device__ __forceinline__ int swz(int row, int piece) { return piece ^ ((row >> 1) & 7); }
-
-struct TileLoc {
-    int expert, row0, rows;  // first sorted row of the tile and its row count (<= BT)
-};
-
-// Tile lookup.  Token tiles are numbered in expert order; feature tile ft of token tile m is work item
-// m * n_ftiles + ft.  Workgroup ids go round-robin over the 8 XCDs, so workgroup b runs on XCD b % 8:
-// each XCD is handed a contiguous eighth of the work items that really exist (their number is only known
-// here, on the device), so that the feature tiles of an expert share one L2 and all XCDs get equal work
-// even though the grid was sized for the worst case.  Every wave computes the same answer.
-template <int BT>
-__device__ __forceinline__ bool locate_tile(const int32_t *__restrict__ offsets, int N, int n_ftiles, TileLoc &loc,
-                                            int &ft)
+// position of logical piece p of row r inside its LDS row (an involution in p)
+template <int KC>
+__device__ __forceinline__ int swz(int row, int piece)
 {
-    const int lane = threadIdx.x & 63;
-    int off[5];
-#pragma unroll
-    for (int q = 0; q < 5; ++q) off[q] = offsets[min(4 * lane + q, N)];
-    int nt[4], local = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        nt[q] = (off[q + 1] - off[q] + BT - 1) / BT;
-        local += nt[q];
-    }
-    int incl = local;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        int v = __shfl_up(incl, o);
-        if (lane >= o) incl += v;
-    }
-    const int items = __shfl(incl, 63) * n_ftiles;
-    const int per_xcd = (items + 7) / 8;
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int item = xcd * per_xcd + j;
-    if (j >= per_xcd || item >= items) return false;
-    const int tile_m = item / n_ftiles;
-    ft = item - tile_m * n_ftiles;
-    int excl = incl - local;
-    const bool mine = tile_m >= excl && tile_m < incl;
-    int e = 0, mt = 0, m = 0, o0 = 0, ntile = 1;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        if (mine && tile_m >= excl && tile_m < excl + nt[q]) {
-            e = 4 * lane + q; mt = tile_m - excl; m = off[q + 1] - off[q]; o0 = off[q]; ntile = nt[q];
-        }
-        excl += nt[q];
-    }
-    const int src = __ffsll((long long)__ballot(mine)) - 1;
-    e = __shfl(e, src); mt = __shfl(mt, src); m = __shfl(m, src); o0 = __shfl(o0, src); ntile = __shfl(ntile, src);
-    // balanced split of the expert's m rows into ntile tiles, each a multiple of 64 rows except the last
-    const int per = (((m + ntile - 1) / ntile) + 63) & ~63;
-    loc.expert = e;
-    loc.row0 = o0 + mt * per;
-    loc.rows = min(per, m - mt * per);
-    return true;
+    return KC == 64 ? (piece ^ ((row >> 1) & 7)) : (piece ^ ((row >> 2) & 3));
 }
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.f + __expf(-g)) * u; }
-
-__device__ __forceinline__ void store4(bf16_t *p, float a, float b, float c, float d)
-{
-    bf16x4 v = {(bf16_t)a, (bf16_t)b, (bf16_t)c, (bf16_t)d};
-    *reinterpret_cast<bf16x4 *>(p) = v;
-}
-__device__ __forceinline__ void store4(float *p, float a, float b, float c, float d)
-{
-    f32x4 v = {a, b, c, d};
-    *reinterpret_cast<f32x4 *>(p) = v;
-}
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
-
-#define ZEDA_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
-#define ZEDA_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
-
-struct TileArgs {
-    const bf16_t *tok, *w0, *w1;
-    const int32_t *sorted_slot;
-    int K, Kdim, Fdim, T;
-    int expert, row0, rows, ft;
-};
-
-// Main loop and epilogue for a tile with GA live 64-row groups (1 <= GA <= G).
-template <class C, bool GATEUP, typename OutT, int GA>
-__device__ __forceinline__ void tile_body(unsigned char *lds, const TileArgs &t, OutT *__restrict__ out)
+// wave-uniform n in 0..8 (a larger n waits as for 8, which is only stricter)
+__device__ __forceinline__ void wait_vmcnt_dyn(int n)
 {
-    constexpr int FB = C::FB, WF = C::WF, BT = C::BT, BF = C::BF, NSTAGE = C::NSTAGE, NW = C::NW, STAGE = C::STAGE;
-    constexpr int NL = C::nl(GA);   // load instructions per wave and chunk
-    constexpr int NTI = 8 * GA;     // ... of the chunk that fetch token rows
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wt = wave / WF, wf = wave % WF;
-    const int col = lane & 31, half = lane >> 5;
-
-    // Source of the piece this lane fetches in each of the wave's NL load instructions per chunk.
-    // Instruction j < NTI covers token rows 8j..8j+7 of the tile, the others weight rows 8(j-NTI)..+7.
-    const bf16_t *src[NL];
-    int dst[NL];
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-        const int j = wave + NW * i;
-        const int piece = lane & 7;
-        if (j < NTI) {
-            const int trow = j * 8 + (lane >> 3);
-            const int r = t.row0 + min(trow, t.rows - 1);  // rows past the tile repeat its last row (never stored)
-            size_t base;
-            if (GATEUP) base = (size_t)min(max(t.sorted_slot[r] / t.K, 0), t.T - 1) * t.Kdim;  // a bad index must not fault
-            else base = (size_t)r * t.Kdim;
-            src[i] = t.tok + base + swz(trow, piece) * 8;
-            dst[i] = j * 1024;
+    if (n >= 4) {
+        if (n >= 6) {
+            if (n >= 8) wait_vmcnt<8>();
+            else if (n == 7) wait_vmcnt<7>();
+            else wait_vmcnt<6>();
         } else {
-            const int row = (j - NTI) * 8 + (lane >> 3);
-            const bf16_t *wbase;
-            int grow;
-            if (GATEUP) {
-                const int blk = (row >> 5) % FB, wfr = row / (32 * FB);
-                grow = t.ft * (BF / 2) + (wfr * (FB / 2) + (blk >> 1)) * 32 + (row & 31);
-                wbase = (blk & 1) ? t.w1 : t.w0;
-            } else {
-                grow = t.ft * BF + row;
-                wbase = t.w0;
-            }
-            src[i] = wbase + ((size_t)t.expert * t.Fdim + grow) * t.Kdim + swz(row, piece) * 8;
-            dst[i] = BT * 128 + (j - NTI) * 1024;
+            if (n == 5) wait_vmcnt<5>();
+            else wait_vmcnt<4>();
         }
-    }
-    auto issue = [&](int chunk) {
-        unsigned char *slot = lds + (chunk % NSTAGE) * STAGE;
-#pragma unroll
-        for (int i = 0; i < NL; ++i)
-            __builtin_amdgcn_global_load_lds(ZEDA_GLOBAL_PTR(src[i] + (size_t)chunk * 64), ZEDA_LDS_PTR(slot + dst[i]), 16, 0,
-                                             0);
-    };
-
-    f32x16 acc[GA][FB];
-#pragma unroll
-    for (int a = 0; a < GA; ++a)
-#pragma unroll
-        for (int b = 0; b < FB; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
-    const int nk = t.Kdim / 64;
-#pragma unroll
-    for (int c = 0; c < NSTAGE - 1; ++c)
-        if (c < nk) issue(c);
-
-    for (int it = 0; it < nk; ++it) {
-        // chunk `it` of this thread has landed once at most NSTAGE-2 later chunks are outstanding
-        if (it + NSTAGE - 2 < nk) wait_vmcnt<(NSTAGE - 2) * NL>();
-        else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();
-        if (it + NSTAGE - 1 < nk) issue(it + NSTAGE - 1);  // refills the slot everyone left before the barrier
-        const unsigned char *cur = lds + (it % NSTAGE) * STAGE;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            bf16x8 fa[FB], tb[GA];
-#pragma unroll
-            for (int b = 0; b < FB; ++b) {
-                const int row = (wf * FB + b) * 32 + col;
-                fa[b] = *reinterpret_cast<const bf16x8 *>(cur + BT * 128 + row * 128 + swz(row, 2 * s + half) * 16);
-            }
-#pragma unroll
-            for (int a = 0; a < GA; ++a) {
-                const int row = (2 * a + wt) * 32 + col;
-                tb[a] = *reinterpret_cast<const bf16x8 *>(cur + row * 128 + swz(row, 2 * s + half) * 16);
-            }
-#pragma unroll
-            for (int a = 0; a < GA; ++a)
-#pragma unroll
-                for (int b = 0; b < FB; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[b], tb[a], acc[a][b], 0, 0, 0);
-        }
-    }
-
-    // acc[a][b][v]: feature 8*(v/4) + 4*half + v%4 of block b, token col of token block 2a + wt
-#pragma unroll
-    for (int a = 0; a < GA; ++a) {
-        const int trow = (2 * a + wt) * 32 + col;
-        if (trow < t.rows) {
-            OutT *orow = out + (size_t)(t.row0 + trow) * t.Fdim + 4 * half;
-            if (GATEUP) {
-#pragma unroll
-                for (int p = 0; p < FB / 2; ++p) {
-                    const int c0 = t.ft * (BF / 2) + (wf * (FB / 2) + p) * 32;
-#pragma unroll
-                    for (int vq = 0; vq < 4; ++vq) {
-                        const f32x16 &g = acc[a][2 * p], &u = acc[a][2 * p + 1];
-                        store4(orow + c0 + 8 * vq, silu_mul(g[4 * vq], u[4 * vq]), silu_mul(g[4 * vq + 1], u[4 * vq + 1]),
-                               silu_mul(g[4 * vq + 2], u[4 * vq + 2]), silu_mul(g[4 * vq + 3], u[4 * vq + 3]));
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int b = 0; b < FB; ++b) {
-                    const int c0 = t.ft * BF + (wf * FB + b) * 32;
-#pragma unroll
-                    for (int vq = 0; vq < 4; ++vq)
-                        store4(orow + c0 + 8 * vq, acc[a][b][4 * vq], acc[a][b][4 * vq + 1], acc[a][b][4 * vq + 2],
-                               acc[a][b][4 * vq + 3]);
-                }
-            }
+    } else {
+        if (n >= 2) {
+            if (n == 3) wait_vmcnt<3>();
+            else wait_vmcnt<2>();
+        } else {
+            if (n == 1) wait_vmcnt<1>();
+            else wait_vmcnt<0>();
         }
     }
 }
 
-template <class C, bool GATEUP, typename OutT, int GA>
-struct TileDispatch {
-    static __device__ __forceinline__ void run(int g, unsigned char *lds, const TileArgs &t, OutT *__restrict__ out)
+// LDS accesses the compiler does not see as such.  It orders every LDS access it knows about behind all
+// global->LDS loads in flight (s_waitcnt vmcnt(0)), which would drain the ring at every table lookup and
+// output transposition; these go around it and wait on lgkmcnt themselves.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(uintptr_t)p; }  // low half of a flat LDS address
+__device__ __forceinline__ uint32_t lds_read_b32(uint32_t a)
+{
+    uint32_t v;
+    asm volatile("ds_read_b32 %0, %1" : "=v"(v) : "v"(a) : "memory");
+    return v;
+}
+__device__ __forceinline__ u32x4 lds_read_b128(uint32_t a)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(a) : "memory");
+    return v;
+}
+__device__ __forceinline__ void lds_write_b64(uint32_t a, u32x2 v)
+{
+    asm volatile("ds_write_b64 %0, %1" ::"v"(a), "v"(v) : "memory");
+}
+// results of the reads above may be used after this
+__device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void lds_wait(uint32_t &a) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a)::"memory"); }
+__device__ __forceinline__ void lds_wait(u32x4 &a) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a)::"memory"); }
+__device__ __forceinline__ void lds_wait(u32x4 &a, u32x4 &b) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b)::"memory"); }
+
+#define ZEDA_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define ZEDA_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+
+// Per-lane view of expert_offsets: lane l holds experts 4l..4l+3, their tile counts and the running total.
+template <int BT>
+struct TileScan {
+    int off[5], nt[4], incl, local, tiles;
+    __device__ __forceinline__ void init(const int32_t *__restrict__ offsets, int N)
     {
-        if (g == GA) tile_body<C, GATEUP, OutT, GA>(lds, t, out);
-        else TileDispatch<C, GATEUP, OutT, GA - 1>::run(g, lds, t, out);
+        const int lane = threadIdx.x & 63;
+#pragma unroll
+        for (int q = 0; q < 5; ++q) off[q] = offsets[min(4 * lane + q, N)];
+        local = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            nt[q] = (off[q + 1] - off[q] + BT - 1) / BT;
+            local += nt[q];
+        }
+        incl = local;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            int v = __shfl_up(incl, o);
+            if (lane >= o) incl += v;
+        }
+        tiles = __shfl(incl, 63);
+    }
+    // (expert, first sorted row, rows, feature tile) of work item `item` = token tile * n_ftiles + feature tile;
+    // the m rows of an expert are split evenly over its tiles, each a multiple of 64 rows except the last.
+    __device__ __forceinline__ int4 locate(int item, int n_ftiles) const
+    {
+        const int lane = threadIdx.x & 63;
+        const int tile_m = item / n_ftiles;
+        const int ft = item - tile_m * n_ftiles;
+        int excl = incl - local;
+        const bool mine = tile_m >= excl && tile_m < incl;
+        int e = 0, mt = 0, m = 0, o0 = 0, ntile = 1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (mine && tile_m >= excl && tile_m < excl + nt[q]) {
+                e = 4 * lane + q; mt = tile_m - excl; m = off[q + 1] - off[q]; o0 = off[q]; ntile = nt[q];
+            }
+            excl += nt[q];
+        }
+        const int src = __ffsll((long long)__ballot(mine)) - 1;
+        e = __shfl(e, src); mt = __shfl(mt, src); m = __shfl(m, src); o0 = __shfl(o0, src); ntile = __shfl(ntile, src);
+        const int per = (((m + ntile - 1) / ntile) + 63) & ~63;
+        return make_int4(e, o0 + mt * per, min(per, m - mt * per), ft);
     }
 };
-template <class C, bool GATEUP, typename OutT>
-struct TileDispatch<C, GATEUP, OutT, 0> {
-    static __device__ __forceinline__ void run(int, unsigned char *, const TileArgs &, OutT *__restrict__) {}
+
+template <class C, bool GATEUP>
+struct Stream {
+    static constexpr int FB = C::FB, WF = C::WF, BT = C::BT, BF = C::BF, NSTAGE = C::NSTAGE, NW = C::NW, STAGE = C::STAGE,
+                         KC = C::KC, KS = C::KS, ROWB = C::ROWB, PPR = C::PPR, RPI = C::RPI, NLMAX = C::NLMAX, NWI = C::NWI;
+    static constexpr int NH = NSTAGE > 2 ? NSTAGE - 2 : 1;
+
+    // kernel arguments
+    const bf16_t *tok, *w0, *w1;
+    bf16_t *out;
+    int Kdim, Fdim, nk;
+    // LDS
+    unsigned char *ring, *stg;
+    const int *s_tok;
+    const int4 *s_loc;
+    // thread position
+    int lane, wave, wt, wf, col, half;
+    int foff_w, foff_t;  // byte offset in a slot of this lane's k-step-0 fragment of weight block 0 / token block wt
+    // issue side: next chunk to fetch is chunk ikc of item iq, into ring slot islot
+    const bf16_t *src[NLMAX];
+    int nq, iq, ikc, islot, inl, inti;
+    int hist[NH];  // load instructions of this wave in each of the last NSTAGE-2 chunks issued
+    // compute side
+    int cslot;
+
+    __device__ __forceinline__ int4 read_loc(int q) const
+    {
+        u32x4 v = lds_read_b128(lds_addr(s_loc + q));
+        lds_wait(v);
+        return make_int4(__builtin_amdgcn_readfirstlane(v[0]), __builtin_amdgcn_readfirstlane(v[1]),
+                         __builtin_amdgcn_readfirstlane(v[2]), __builtin_amdgcn_readfirstlane(v[3]));
+    }
+    __device__ __forceinline__ void setup_issue_item()
+    {
+        if (iq >= nq) { inl = 0; return; }
+        const int4 loc = read_loc(iq);
+        const int expert = loc.x, rows = loc.z, ft = loc.w;
+        const int g = (rows + 63) >> 6;
+        inti = g * (64 / RPI);
+        const int total = inti + NWI;
+        inl = min(NLMAX, max(0, (total - wave + NW - 1) / NW));
+        int ln = lane;
+        asm volatile("" : "+v"(ln));  // (recomputed per item rather than kept live)
+        const int piece = ln % PPR, rsub = ln / PPR;
+        uint32_t srow[NLMAX];
+#pragma unroll
+        for (int i = 0; i < NLMAX; ++i)  // (instructions that fetch weights read an entry too, and ignore it)
+            srow[i] = lds_read_b32(lds_addr(s_tok + iq * BT + min(wave + NW * i, inti - 1) * RPI + rsub));
+#pragma unroll
+        for (int i = 0; i < NLMAX; ++i) lds_wait(srow[i]);
+#pragma unroll
+        for (int i = 0; i < NLMAX; ++i) {
+            const int j = wave + NW * i;
+            if (j < inti) {
+                const int trow = j * RPI + rsub;
+                src[i] = tok + (size_t)srow[i] * Kdim + swz<KC>(trow, piece) * 8;
+            } else {
+                const int row = min(j - inti, NWI - 1) * RPI + rsub;  // (the clamp only keeps unused entries in range)
+                const bf16_t *wbase;
+                int grow;
+                if (GATEUP) {
+                    const int blk = (row >> 5) % FB, wfr = row / (32 * FB);
+                    grow = ft * (BF / 2) + (wfr * (FB / 2) + (blk >> 1)) * 32 + (row & 31);
+                    wbase = (blk & 1) ? w1 : w0;
+                } else {
+                    grow = ft * BF + row;
+                    wbase = w0;
+                }
+                src[i] = wbase + ((size_t)expert * Fdim + grow) * Kdim + swz<KC>(row, piece) * 8;
+            }
+        }
+    }
+    // load instruction i of the chunk being issued (i < ni, wave-uniform)
+    __device__ __forceinline__ void issue_one(int i, int ni)
+    {
+        if (i < ni) {
+            const int j = wave + NW * i;
+            const int dst = j * 1024 + (j >= inti ? BT * ROWB - inti * 1024 : 0);
+            __builtin_amdgcn_global_load_lds(ZEDA_GLOBAL_PTR(src[i] + (size_t)ikc * KC),
+                                             ZEDA_LDS_PTR(ring + islot * STAGE + dst), 16, 0, 0);
+        }
+    }
+    // bookkeeping after the instructions of one chunk were issued (ni of them; 0 once the stream has ended)
+    __device__ __forceinline__ void issued(int ni)
+    {
+#pragma unroll
+        for (int h = 0; h + 1 < NH; ++h) hist[h] = hist[h + 1];
+        hist[NH - 1] = ni;
+        if (iq < nq) {
+            islot = islot + 1 == NSTAGE ? 0 : islot + 1;
+            if (++ikc == nk) {
+                ikc = 0;
+                ++iq;
+                setup_issue_item();
+            }
+        }
+    }
+    __device__ __forceinline__ void issue_burst()
+    {
+        const int ni = inl;
+#pragma unroll
+        for (int i = 0; i < NLMAX; ++i) issue_one(i, ni);
+        issued(ni);
+    }
+    // this wave's loads of the oldest chunk in flight have landed
+    __device__ __forceinline__ void wait_oldest()
+    {
+        if (NSTAGE == 2) {
+            wait_vmcnt<0>();
+        } else {
+            int w = 0;
+#pragma unroll
+            for (int h = 0; h < NH; ++h) w += hist[h];
+            wait_vmcnt_dyn(w);
+        }
+    }
+
+    // Fragments of k step s of the chunk in `slot`: FB weight blocks of this wave column, GA token blocks of this
+    // wave row.  Blocks start at multiples of 32 rows, so the piece permutation depends on `col` only and the
+    // address is one per-lane term (foff, XOR 32*s) plus block offsets that are immediates.
+    template <int GA>
+    __device__ __forceinline__ void load_frags(const unsigned char *slot, int s, bf16x8 (&fa)[FB], bf16x8 (&tb)[GA]) const
+    {
+        const unsigned char *pw = slot + (foff_w ^ (s << 5)), *pt = slot + (foff_t ^ (s << 5));
+#pragma unroll
+        for (int b = 0; b < FB; ++b) fa[b] = *reinterpret_cast<const bf16x8 *>(pw + b * 32 * ROWB);
+#pragma unroll
+        for (int a = 0; a < GA; ++a) tb[a] = *reinterpret_cast<const bf16x8 *>(pt + a * 64 * ROWB);
+    }
+
+    // One item with GA live 64-row groups: its nk chunks, then the epilogue.
+    template <int GA>
+    __device__ __forceinline__ void tile_body(int expert, int row0, int rows, int ft)
+    {
+        f32x16 acc[GA][FB];
+#pragma unroll
+        for (int a = 0; a < GA; ++a)
+#pragma unroll
+            for (int b = 0; b < FB; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+        // first chunk of the item: wait, meet, refill the slot everybody has just left
+        wait_oldest();
+        __builtin_amdgcn_s_barrier();
+        issue_burst();
+        bf16x8 fa[2][FB], tb[2][GA];
+        load_frags<GA>(ring + cslot * STAGE, 0, fa[0], tb[0]);
+
+        for (int kc = 0; kc < nk; ++kc) {
+            const unsigned char *cur = ring + cslot * STAGE;
+            const int nslot = cslot + 1 == NSTAGE ? 0 : cslot + 1;
+            const bool more = kc + 1 < nk;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const int p = s & 1;
+                int ni = 0;
+                if (s < KS - 1) {
+                    load_frags<GA>(cur, s + 1, fa[p ^ 1], tb[p ^ 1]);
+                } else {
+                    // every fragment of this chunk is in registers: nobody needs its slot any more
+                    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+                    if (more) {
+                        wait_oldest();
+                        __builtin_amdgcn_s_barrier();
+                        load_frags<GA>(ring + nslot * STAGE, 0, fa[p ^ 1], tb[p ^ 1]);
+                        ni = inl;
+                    }
+                }
+                // keep the reads of the next step ahead of this step's MFMAs
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int a = 0; a < GA; ++a)
+#pragma unroll
+                    for (int b = 0; b < FB; ++b) {
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[p][b], tb[p][a], acc[a][b], 0, 0, 0);
+                        if (s == KS - 1) {
+                            // the refill of the slot freed by the barrier, spread over this step's MFMAs
+                            constexpr int NM = GA * FB;
+                            const int m = a * FB + b;
+#pragma unroll
+                            for (int i = 0; i < NLMAX; ++i)
+                                if (i * NM / NLMAX == m) issue_one(i, ni);
+                        }
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+                if (s == KS - 1 && more) issued(ni);
+            }
+            cslot = nslot;
+        }
+
+        // Epilogue.  acc[a][b][v] is feature 8*(v/4) + 4*half + v%4 of weight block b, token `col` of token
+        // block 2a + wt.  Each 32x32 result block goes through this wave's LDS buffer (rows of 32 bf16, pieces
+        // permuted by the row) and leaves as 16 bytes per lane, four lanes to a token row.
+        constexpr int NOB = GATEUP ? FB / 2 : FB;
+        int ln = lane;
+        asm volatile("" : "+v"(ln));  // (keeps the address arithmetic below out of the main loop's registers)
+        const int ecol = ln & 31, ehalf = ln >> 5;
+        // staging buffer: token row `ecol` holds 32 features as 4 pieces of 16 bytes, piece p at position
+        // p ^ ((row >> 2) & 3); a lane writes the half `ehalf` of piece vq and reads piece ln & 3 of rows ln >> 2, + 16
+        const uint32_t stg_w = lds_addr(stg) + ecol * 64 + ((ecol >> 2) & 3) * 16 + ehalf * 8;
+        const uint32_t stg_r = lds_addr(stg) + (ln >> 2) * 64 + ((ln & 3) ^ ((ln >> 4) & 3)) * 16;
+#pragma unroll
+        for (int a = 0; a < GA; ++a) {
+            const int trow0 = (2 * a + wt) * 32;
+            if (trow0 < rows) {
+#pragma unroll
+                for (int ob = 0; ob < NOB; ++ob) {
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        bf16x4 v;
+                        if (GATEUP) {
+                            const f32x16 &g = acc[a][2 * ob], &u = acc[a][2 * ob + 1];
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) v[k] = (bf16_t)silu_mul(g[4 * vq + k], u[4 * vq + k]);
+                        } else {
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) v[k] = (bf16_t)acc[a][ob][4 * vq + k];
+                        }
+                        lds_write_b64(stg_w ^ (vq << 4), __builtin_bit_cast(u32x2, v));
+                    }
+                    const int c0 = GATEUP ? ft * (BF / 2) + (wf * (FB / 2) + ob) * 32 : ft * BF + (wf * FB + ob) * 32;
+                    u32x4 o0 = lds_read_b128(stg_r), o1 = lds_read_b128(stg_r + 16 * 64);
+                    lds_wait(o0, o1);
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const int r = 16 * i + (ln >> 2), pc = ln & 3;
+                        if (trow0 + r < rows)
+                            *reinterpret_cast<u32x4 *>(out + (size_t)(row0 + trow0 + r) * Fdim + c0 + pc * 8) = i ? o1 : o0;
+                        // (a non-empty block after the per-lane branch: if that branch joined straight into a loop
+                        // header the compiler would treat all the wave-uniform stream state as divergent)
+                        asm volatile("" ::: "memory");
+                    }
+                }
+            }
+        }
+    }
+};
+
+template <class C, bool GATEUP, int GA>
+struct TileDispatch {
+    static __device__ __forceinline__ void run(Stream<C, GATEUP> &st, int g, int expert, int row0, int rows, int ft)
+    {
+        if (g == GA) st.template tile_body<GA>(expert, row0, rows, ft);
+        else TileDispatch<C, GATEUP, GA - 1>::run(st, g, expert, row0, rows, ft);
+    }
+};
+template <class C, bool GATEUP>
+struct TileDispatch<C, GATEUP, 0> {
+    static __device__ __forceinline__ void run(Stream<C, GATEUP> &, int, int, int, int, int) {}
 };
 
 // GATEUP: tok = x[T,Kdim], w0 = W_gate[N,Fdim,Kdim], w1 = W_up, out = act[S,Fdim] (Fdim = I, Kdim = H).
 // DOWN:   tok = act[S,Kdim], w0 = W_down[N,Fdim,Kdim], out = y_slot[S,Fdim]        (Fdim = H, Kdim = I).
-// Kdim is a multiple of 64; Fdim a multiple of the feature tile (BF/2 for GATEUP, BF for DOWN).
-template <class C, bool GATEUP, typename OutT>
+// Kdim is a multiple of KC; Fdim a multiple of the feature tile (BF/2 for GATEUP, BF for DOWN).
+// The grid is a multiple of 8 workgroups.
+template <class C, bool GATEUP>
 __global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__restrict__ tok,
                                                               const bf16_t *__restrict__ w0,
                                                               const bf16_t *__restrict__ w1,
                                                               const int32_t *__restrict__ offsets,
                                                               const int32_t *__restrict__ sorted_slot,
-                                                              OutT *__restrict__ out, int N, int K, int Kdim, int Fdim,
+                                                              bf16_t *__restrict__ out, int N, int K, int Kdim, int Fdim,
                                                               int n_ftiles, int T)
 {
     static_assert(!GATEUP || C::FB % 2 == 0, "gate and up blocks come in pairs");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    int *s_tok = reinterpret_cast<int *>(lds + C::TOK_OFF);
+    int4 *s_loc = reinterpret_cast<int4 *>(lds + C::LOC_OFF);
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    TileLoc loc;
-    int ft;
-    if (!locate_tile<C::BT>(offsets, N, n_ftiles, loc, ft)) return;
-    TileArgs t;
-    t.tok = tok; t.w0 = w0; t.w1 = w1; t.sorted_slot = sorted_slot;
-    t.K = K; t.Kdim = Kdim; t.Fdim = Fdim; t.T = T; t.ft = ft;
-    // the tile is the same for every lane: keep it in scalar registers
-    t.expert = __builtin_amdgcn_readfirstlane(loc.expert);
-    t.row0 = __builtin_amdgcn_readfirstlane(loc.row0);
-    t.rows = __builtin_amdgcn_readfirstlane(loc.rows);
-    const int g = (t.rows + 63) >> 6;  // live 64-row groups, 1..G
-    TileDispatch<C, GATEUP, OutT, C::G>::run(g, lds, t, out);
-}
+    // the work items of this workgroup: first + i * stride below end
+    const int wgs = gridDim.x >> 3, xcd = blockIdx.x & 7, wg = blockIdx.x >> 3;
+    int mine, first;
+    {
+        TileScan<C::BT> sc;
+        sc.init(offsets, N);
+        const int items = sc.tiles * n_ftiles, per_xcd = (items + 7) / 8;
+        const int lo = xcd * per_xcd, hi = min(lo + per_xcd, items);
+        first = lo + wg;
+        mine = first < hi ? (hi - first + wgs - 1) / wgs : 0;
+    }
+    mine = __builtin_amdgcn_readfirstlane(mine); first = __builtin_amdgcn_readfirstlane(first);
 
-// worst-case number of workgroups: sum over experts of ceil(m_e / BT) with m_e <= T and sum m_e <= T*K
-template <class C>
-inline int ffn_grid(int T, int K, int N, int n_ftiles)
-{
-    const int64_t S = (int64_t)T * K;
-    int64_t tiles_m = (int64_t)N * ((T + C::BT - 1) / C::BT);
-    const int64_t alt = S / C::BT + N;
-    if (alt < tiles_m) tiles_m = alt;
-    const int64_t g = tiles_m * n_ftiles;
-    return (int)((g + 7) / 8 * 8);
+    for (int q0 = 0; q0 < mine; q0 += C::MAXQ) {
+        const int nq = min(C::MAXQ, mine - q0);
+        if (q0 > 0) __syncthreads();  // everybody has left the tables and the ring of the batch before
+        {
+            TileScan<C::BT> sc;
+            sc.init(offsets, N);
+            for (int q = wave; q < nq; q += C::NW) {
+                const int4 loc = sc.locate(first + (q0 + q) * wgs, n_ftiles);
+                if (lane == 0) s_loc[q] = loc;
+            }
+        }
+        __syncthreads();
+        for (int idx = tid; idx < nq * C::BT; idx += C::THREADS) {
+            const int q = idx / C::BT, r = idx - q * C::BT;
+            const int4 loc = s_loc[q];
+            const int rr = loc.y + min(r, loc.z - 1);  // rows past the tile repeat its last row (never stored)
+            s_tok[idx] = GATEUP ? min(max(sorted_slot[rr] / K, 0), T - 1) : rr;  // a bad index must not fault
+        }
+        __syncthreads();
+
+        Stream<C, GATEUP> st;
+        st.tok = tok; st.w0 = w0; st.w1 = w1; st.out = out;
+        st.Kdim = Kdim; st.Fdim = Fdim; st.nk = Kdim / C::KC;
+        st.ring = lds; st.stg = lds + C::STG_OFF + wave * 2048; st.s_tok = s_tok; st.s_loc = s_loc;
+        st.lane = lane; st.wave = wave; st.wt = wave / C::WF; st.wf = wave % C::WF; st.col = lane & 31; st.half = lane >> 5;
+        st.foff_t = (st.wt * 32 + st.col) * C::ROWB + swz<C::KC>(st.col, st.half) * 16;
+        st.foff_w = (C::BT + st.wf * C::FB * 32 + st.col) * C::ROWB + swz<C::KC>(st.col, st.half) * 16;
+        st.nq = nq; st.iq = 0; st.ikc = 0; st.islot = 0; st.cslot = 0; st.inl = 0; st.inti = 0;
+#pragma unroll
+        for (int h = 0; h < Stream<C, GATEUP>::NH; ++h) st.hist[h] = 0;
+        st.setup_issue_item();
+#pragma unroll
+        for (int c = 0; c < C::NSTAGE - 1; ++c) st.issue_burst();
+        // hist now covers the NSTAGE-2 newest chunks; the oldest one is what the first wait is for
+
+        for (int q = 0; q < nq; ++q) {
+            const int4 loc = st.read_loc(q);
+            TileDispatch<C, GATEUP, C::G>::run(st, (loc.z + 63) >> 6, loc.x, loc.y, loc.z, loc.w);
+        }
+    }
 }
 
 }  // namespace zeda
