@@ -16,7 +16,8 @@
  *     The library allocates nothing, frees nothing and never synchronises: all work is enqueued on
  *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and the call returns.
  *   - Matrices are dense row-major with the reduction dimension contiguous:
- *     x[T,H], w_router[N+Z,H], w_gate[N,I,H], w_up[N,I,H], w_down[N,H,I], out[T,H].
+ *     x[T,H], w_router[N+Z,H], w_gate[N,I,H], w_up[N,I,H], w_down[N,H,I], out[T,H]
+ *     (the three expert tensors may instead be in the tiled layout, see zeda_weight_layout).
  *     Their element type is desc->dtype (fp32, or bf16 with fp32 accumulation).  Indices are int32,
  *     routing weights fp32.
  *   - Inputs are never written.  Outputs are fully overwritten.
@@ -39,7 +40,7 @@ extern "C" {
 typedef enum {
     ZEDA_OK = 0,
     ZEDA_EINVAL = -1,       /* NULL required pointer, misaligned pointer, T<0, K<1, K>N+Z, N<1, Z<0, bad enum */
-    ZEDA_EUNSUPPORTED = -2, /* valid layer, outside the shape limits above */
+    ZEDA_EUNSUPPORTED = -2, /* valid layer, outside the shape limits above; tiled weights with fp32 */
     ZEDA_EWORKSPACE = -3,   /* workspace smaller than the matching *_workspace_bytes() */
     ZEDA_EHIP = -4          /* a kernel launch failed (hipGetLastError) */
 } zeda_status;
@@ -56,6 +57,12 @@ typedef enum {
     ZEDA_GATE_REAL_RENORM = 2 /* g = p_i / sum of p over the selected normal experts (Eq. 7) */
 } zeda_gate_norm;
 
+/* Storage of the expert weights w_gate, w_up, w_down (the router weights are always row-major).
+ * ZEDA_WEIGHTS_TILED is what zeda_pack_expert_weights writes: same size, 32x32 blocks laid out so that the
+ * expert GEMM fetches them with long contiguous reads; weights are static, so they are packed once when
+ * they are loaded.  bf16 only. */
+typedef enum { ZEDA_WEIGHTS_ROW_MAJOR = 0, ZEDA_WEIGHTS_TILED = 1 } zeda_weight_layout;
+
 typedef struct {
     int32_t T;         /* tokens in this call                      */
     int32_t H;         /* hidden size                              */
@@ -65,6 +72,7 @@ typedef struct {
     int32_t K;         /* slots per token                          */
     int32_t dtype;     /* zeda_dtype of x, weights, out            */
     int32_t gate_norm; /* zeda_gate_norm                           */
+    int32_t weight_layout; /* zeda_weight_layout of w_gate, w_up, w_down */
 } zeda_layer_desc;
 
 /* Short name of a status code (host pointer to a static string). */
@@ -132,6 +140,17 @@ int zeda_moe_forward_events(const zeda_layer_desc *desc, const void *x, const vo
                             const float *router_bias, const void *w_gate, const void *w_up, const void *w_down,
                             void *out, int32_t *num_real_out, void *ws, size_t ws_bytes, void *stream,
                             void *const *events /* host: hipEvent_t[ZEDA_NUM_STAGES + 1] */);
+
+/* Rewrites the expert weights of a layer from row-major into ZEDA_WEIGHTS_TILED (one-time, outside the hot
+ * path; the layer of Section 2.1 does not depend on how its weights are stored).  For a matrix W[F][Kd]
+ * (W_gate[e], W_up[e]: F = I, Kd = H; W_down[e]: F = H, Kd = I) the output holds (F/32) x (Kd/32) blocks of
+ * 2 KiB, block (rb, kb) at index rb * (Kd/32) + kb; a block stores rows 32rb.., columns 32kb.. as 32 rows of
+ * 64 bytes whose four 16-byte pieces are permuted: piece p of row r sits at position p ^ ((r >> 2) & 3).
+ * Experts follow each other as in the input.  Any of the three pairs may be NULL/NULL (skipped); in and out
+ * must not overlap.  desc->dtype must be bf16 (ZEDA_EUNSUPPORTED otherwise); desc->T and weight_layout are
+ * ignored. */
+int zeda_pack_expert_weights(const zeda_layer_desc *desc, const void *w_gate, const void *w_up, const void *w_down,
+                             void *w_gate_tiled, void *w_up_tiled, void *w_down_tiled, void *stream);
 
 /* Byte offsets inside the forward workspace (host-only).  Returns ZEDA_OK or an error. */
 typedef struct {

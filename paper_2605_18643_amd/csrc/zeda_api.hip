@@ -11,11 +11,13 @@ int check_desc(const zeda_layer_desc *d)
     if ((int64_t)d->K > (int64_t)d->N + d->Z) return ZEDA_EINVAL;
     if (d->dtype != ZEDA_F32 && d->dtype != ZEDA_BF16) return ZEDA_EINVAL;
     if (d->gate_norm < ZEDA_GATE_SOFTMAX || d->gate_norm > ZEDA_GATE_REAL_RENORM) return ZEDA_EINVAL;
+    if (d->weight_layout != ZEDA_WEIGHTS_ROW_MAJOR && d->weight_layout != ZEDA_WEIGHTS_TILED) return ZEDA_EINVAL;
     if ((int64_t)d->N + d->Z > kMaxExperts || d->K > kMaxK) return ZEDA_EUNSUPPORTED;
     if ((int64_t)d->T * d->K >= (1 << 24)) return ZEDA_EUNSUPPORTED;
     if (d->dtype == ZEDA_BF16) {
         if (d->H % 128 != 0 || d->I % 64 != 0) return ZEDA_EUNSUPPORTED;
     } else {
+        if (d->weight_layout != ZEDA_WEIGHTS_ROW_MAJOR) return ZEDA_EUNSUPPORTED;
         if (d->H % 4 != 0 || d->I % 4 != 0 || d->H > 12288 || d->I > 12288) return ZEDA_EUNSUPPORTED;
     }
     return ZEDA_OK;
@@ -224,6 +226,34 @@ int zeda_moe_forward_events(const zeda_layer_desc *desc, const void *x, const vo
         if (!events[i]) return ZEDA_EINVAL;
     return forward_impl(desc, x, w_router, router_bias, w_gate, w_up, w_down, out, num_real_out, ws, ws_bytes, stream,
                         events);
+}
+
+int zeda_pack_expert_weights(const zeda_layer_desc *desc, const void *w_gate, const void *w_up, const void *w_down,
+                             void *w_gate_tiled, void *w_up_tiled, void *w_down_tiled, void *stream)
+{
+    if (!desc) return ZEDA_EINVAL;
+    zeda_layer_desc d = *desc;
+    d.T = 0;
+    d.weight_layout = ZEDA_WEIGHTS_ROW_MAJOR;
+    int rc = check_desc(&d);
+    if (rc != ZEDA_OK) return rc;
+    if (d.dtype != ZEDA_BF16) return ZEDA_EUNSUPPORTED;
+    const void *in[3] = {w_gate, w_up, w_down};
+    void *out[3] = {w_gate_tiled, w_up_tiled, w_down_tiled};
+    const size_t bytes = (size_t)d.N * d.I * d.H * 2;
+    for (int i = 0; i < 3; ++i) {
+        if ((in[i] == nullptr) != (out[i] == nullptr)) return ZEDA_EINVAL;
+        if (!in[i]) continue;
+        if (!aligned16(in[i]) || !aligned16(out[i])) return ZEDA_EINVAL;
+        const char *a = (const char *)in[i], *b = (const char *)out[i];
+        if (a < b + bytes && b < a + bytes) return ZEDA_EINVAL;  // overlap
+    }
+    for (int i = 0; i < 3; ++i) {
+        if (!in[i]) continue;
+        rc = launch_pack_weights(&d, in[i], out[i], /*down=*/i == 2, (hipStream_t)stream);
+        if (rc != ZEDA_OK) return rc;
+    }
+    return ZEDA_OK;
 }
 
 }  // extern "C"

@@ -86,19 +86,22 @@ __global__ __launch_bounds__(kF32Threads) void ffn_f32_down_kernel(const float *
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
-//              G FB WF NSTAGE KC
-typedef TileCfg<4, 2, 4, 2, 64> CfgPrefill;  // 256 tokens x 256 weight rows, 8 waves, one workgroup per CU
-typedef TileCfg<4, 2, 2, 2, 64> CfgNarrow;   // 256 tokens x 128 weight rows, 4 waves: any H % 128 == 0, I % 64 == 0
-typedef TileCfg<1, 2, 2, 4, 32> CfgDecode;   // 64 tokens x 128 weight rows, 4 waves, four chunks deep, two per CU
+//              G FB WF NSW NST KC   (NSW, NST: depth of the weight and of the token ring)
+typedef TileCfg<4, 2, 4, 2, 2, 64> CfgPrefill;  // 256 tokens x 256 weight rows, 8 waves, one workgroup per CU
+typedef TileCfg<4, 2, 2, 2, 2, 64> CfgNarrow;   // 256 tokens x 128 weight rows, 4 waves: any H % 128 == 0, I % 64 == 0
+typedef TileCfg<1, 2, 2, 4, 4, 32> CfgDecode;   // 64 tokens x 128 weight rows, 4 waves, two workgroups per CU
+// tiled weights come in 32-wide k blocks: 32-wide chunks, four deep
+typedef TileCfg<4, 2, 4, 4, 4, 32> CfgPrefillT;
+typedef TileCfg<4, 2, 2, 4, 4, 32> CfgNarrowT;
 
 // Persistent grid: as many workgroups as the device holds at once, rounded down to a multiple of 8 so that
 // every XCD gets the same number (the kernel reads the count from gridDim).
-template <class C, bool GATEUP>
+template <class C, bool GATEUP, bool TILED>
 static int resident_grid()
 {
     static int grid = 0;  // per instantiation; idempotent, so a race between host threads is harmless
     if (grid == 0) {
-        auto kern = ffn_bf16_kernel<C, GATEUP>;
+        auto kern = ffn_bf16_kernel<C, GATEUP, TILED>;
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
@@ -111,15 +114,15 @@ static int resident_grid()
     return grid;
 }
 
-template <class C, bool GATEUP>
+template <class C, bool GATEUP, bool TILED>
 static int launch_tile_kernel(const zeda_layer_desc *d, const void *tok, const void *w0, const void *w1,
                               const int32_t *offsets, const int32_t *sorted_slot, void *out, hipStream_t s)
 {
-    const int grid = resident_grid<C, GATEUP>();
+    const int grid = resident_grid<C, GATEUP, TILED>();
     if (grid == 0) return ZEDA_EHIP;
     const int Kdim = GATEUP ? d->H : d->I, Fdim = GATEUP ? d->I : d->H;
     const int n_ftiles = GATEUP ? Fdim / (C::BF / 2) : Fdim / C::BF;
-    ffn_bf16_kernel<C, GATEUP><<<grid, C::THREADS, C::LDS_BYTES, s>>>((const bf16_t *)tok, (const bf16_t *)w0,
+    ffn_bf16_kernel<C, GATEUP, TILED><<<grid, C::THREADS, C::LDS_BYTES, s>>>((const bf16_t *)tok, (const bf16_t *)w0,
                                                                      (const bf16_t *)w1, offsets, sorted_slot,
                                                                      (bf16_t *)out, d->N, d->K, Kdim, Fdim, n_ftiles, d->T);
     return last_launch_status();
@@ -137,11 +140,25 @@ static int launch_bf16(const zeda_layer_desc *d, const void *tok, const void *w0
                        const int32_t *sorted_slot, void *out, hipStream_t s)
 {
     // an expert never has more rows than there are tokens: small batches take the short token tile
-    if (d->T <= CfgDecode::BT && cfg_fits<CfgDecode>(d))
-        return launch_tile_kernel<CfgDecode, GATEUP>(d, tok, w0, w1, offsets, sorted_slot, out, s);
+    const bool decode = d->T <= CfgDecode::BT && cfg_fits<CfgDecode>(d);
+    if (d->weight_layout == ZEDA_WEIGHTS_TILED) {
+        if (decode) return launch_tile_kernel<CfgDecode, GATEUP, true>(d, tok, w0, w1, offsets, sorted_slot, out, s);
+        if (cfg_fits<CfgPrefillT>(d))
+            return launch_tile_kernel<CfgPrefillT, GATEUP, true>(d, tok, w0, w1, offsets, sorted_slot, out, s);
+        return launch_tile_kernel<CfgNarrowT, GATEUP, true>(d, tok, w0, w1, offsets, sorted_slot, out, s);
+    }
+    if (decode) return launch_tile_kernel<CfgDecode, GATEUP, false>(d, tok, w0, w1, offsets, sorted_slot, out, s);
     if (cfg_fits<CfgPrefill>(d))
-        return launch_tile_kernel<CfgPrefill, GATEUP>(d, tok, w0, w1, offsets, sorted_slot, out, s);
-    return launch_tile_kernel<CfgNarrow, GATEUP>(d, tok, w0, w1, offsets, sorted_slot, out, s);
+        return launch_tile_kernel<CfgPrefill, GATEUP, false>(d, tok, w0, w1, offsets, sorted_slot, out, s);
+    return launch_tile_kernel<CfgNarrow, GATEUP, false>(d, tok, w0, w1, offsets, sorted_slot, out, s);
+}
+
+int launch_pack_weights(const zeda_layer_desc *d, const void *w, void *out, bool down, hipStream_t s)
+{
+    const int F = down ? d->H : d->I, Kd = down ? d->I : d->H;
+    const size_t pieces = (size_t)d->N * F * Kd / 8;
+    pack_weights_kernel<<<(unsigned)((pieces + 255) / 256), 256, 0, s>>>((const bf16_t *)w, (bf16_t *)out, F, Kd, pieces);
+    return last_launch_status();
 }
 
 int launch_gateup(const zeda_layer_desc *d, const void *x, const void *wg, const void *wu, const int32_t *offsets,

@@ -11,18 +11,20 @@
 // every tile row to LDS; after that the main stream touches global memory only through global->LDS loads
 // and the output stores.
 //
-// One continuous stream of chunks.  Both operand tiles move through an NSTAGE-deep ring in LDS in KC-wide
-// k chunks, fetched with global->LDS loads (no staging registers): one wave instruction moves 64 pieces of
-// 16 bytes to 1 KiB of consecutive LDS, so lane l fetches the piece that belongs at position l of that
-// KiB.  The pieces of a row are XOR-permuted by the row index so that the 16 rows a fragment read touches
-// per phase fall on distinct banks; the permutation is applied on the global address.  The chunks of all
-// items of a workgroup form ONE sequence: while the last chunks of an item are multiplied and its result
-// is written, the first chunks of the next item are already in flight, so HBM never sees the pipeline
-// drain between tiles.  Per chunk there is one counted s_waitcnt (this wave's own loads of that chunk)
-// and one s_barrier (everybody's loads have landed, and everybody has left the slot that is refilled
-// next).  The refill is issued a few instructions at a time between the MFMAs that follow the barrier,
-// so that the texture path never sees all waves issue at once; fragments are double-buffered in
-// registers and read one k step ahead.
+// One continuous stream of chunks.  The weight tile and the token tile each move through a ring of slots in
+// LDS (NSW and NST deep) in KC-wide k chunks, fetched with global->LDS loads (no staging registers): one
+// wave instruction moves 64 pieces of 16 bytes to 1 KiB of consecutive LDS, so lane l fetches the piece
+// that belongs at position l of that KiB.  The pieces of a row are XOR-permuted by the row index so that
+// the 16 rows a fragment read touches per phase fall on distinct banks; the permutation is applied on the
+// global address (or is already part of the stored layout, for tiled weights).  Half of the waves fetch
+// weight rows only and the other half token rows only, so every wave's vmcnt counts one stream and the two
+// rings may have different depths.  The chunks of all items of a workgroup form ONE sequence: while the
+// last chunks of an item are multiplied and its result is written, the first chunks of the next item are
+// already in flight, so HBM never sees the pipeline drain between tiles.  Per chunk there is one counted
+// s_waitcnt (this wave's own loads of that chunk) and one s_barrier (everybody's loads have landed, and
+// everybody has left the slots that are refilled next).  The refill is issued a few instructions at a
+// time between the MFMAs that follow the barrier, so that the texture path never sees all waves issue at
+// once; fragments are double-buffered in registers and read one k step ahead.
 //
 // Only the 64-row groups of a token tile that hold rows are fetched and multiplied (their number is a
 // template parameter of the tile body, so the MFMA loop has no branches), and the two wave rows take
@@ -33,30 +35,35 @@
 
 namespace zeda {
 
-template <int G_, int FB_, int WF_, int NSTAGE_, int KC_>
+template <int G_, int FB_, int WF_, int NSW_, int NST_, int KC_>
 struct TileCfg {
-    static constexpr int G = G_, FB = FB_, WF = WF_, NSTAGE = NSTAGE_, KC = KC_;
+    static constexpr int G = G_, FB = FB_, WF = WF_, NSW = NSW_, NST = NST_, KC = KC_;
     static constexpr int WT = 2;                  // wave rows: wave row wt owns token blocks wt, wt+2, ...
     static constexpr int BT = 64 * G;             // tokens per tile
     static constexpr int BF = 32 * FB * WF;       // weight rows per tile (gate and up rows both count)
     static constexpr int NW = WT * WF;            // waves
+    static constexpr int NWW = NW / 2;            // waves 0..NWW-1 fetch the weight rows, the others the token rows
+    static constexpr int NWT = NW - NWW;
     static constexpr int THREADS = 64 * NW;
     static constexpr int ROWB = 2 * KC;           // bytes of one row of a chunk
     static constexpr int PPR = ROWB / 16;         // 16-byte pieces per row
     static constexpr int RPI = 64 / PPR;          // rows covered by one wave load instruction
     static constexpr int KS = KC / 16;            // MFMA k steps per chunk
-    static constexpr int STAGE = (BT + BF) * ROWB;
-    static constexpr int RING = NSTAGE * STAGE;
-    static constexpr int NWI = BF / RPI;          // load instructions per chunk that fetch weight rows
-    static constexpr int nti(int g) { return 64 * g / RPI; }  // ... that fetch the rows of g live token groups
-    static constexpr int NLMAX = (nti(G) + NWI + NW - 1) / NW;  // most load instructions per wave and chunk
+    static constexpr int WST = BF * ROWB, TST = BT * ROWB;  // bytes of a weight / token ring slot
+    static constexpr int WRING = NSW * WST, TRING = NST * TST;
+    static constexpr int NLW = BF / RPI / NWW;    // load instructions per chunk of a weight wave
+    static constexpr int nlt(int g) { return 64 * g / RPI / NWT; }  // ... of a token wave with g live 64-row groups
+    static constexpr int NLMAX = NLW > nlt(G) ? NLW : nlt(G);
     static constexpr int MAXQ = 8;                // items looked up at a time
-    static constexpr int TOK_OFF = RING;                     // int32 [MAXQ][BT]: source row of every tile row
+    static constexpr int TRING_OFF = WRING;
+    static constexpr int TOK_OFF = WRING + TRING;            // int32 [MAXQ][BT]: source row of every tile row
     static constexpr int LOC_OFF = TOK_OFF + MAXQ * BT * 4;  // int4  [MAXQ]: expert, row0, rows, feature tile
     static constexpr int STG_OFF = LOC_OFF + MAXQ * 16;      // 2 KiB per wave: output transposition
     static constexpr int LDS_BYTES = STG_OFF + NW * 2048;
+    static constexpr int WMAX = (NSW - 2) * NLW > (NST - 2) * nlt(G) ? (NSW - 2) * NLW : (NST - 2) * nlt(G);
     static_assert(KC == 32 || KC == 64, "rows of 64 or 128 bytes");
-    static_assert(NSTAGE >= 2 && (NSTAGE - 1) * NLMAX <= 63, "vmcnt is a 6-bit counter");
+    static_assert((BF / RPI) % NWW == 0 && (64 / RPI) % NWT == 0, "loads must divide evenly over the waves of a role");
+    static_assert(NSW >= 2 && NST >= 2 && (NSW - 1) * NLW <= 63 && (NST - 1) * nlt(G) <= 63, "vmcnt is a 6-bit counter");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS is 160 KiB per CU");
 };
 
@@ -74,26 +81,16 @@ __device__ __forceinline__ void wait_vmcnt()
 {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
-// wave-uniform n in 0..8 (a larger n waits as for 8, which is only stricter)
-__device__ __forceinline__ void wait_vmcnt_dyn(int n)
+// s_waitcnt vmcnt(n) for a wave-uniform n in LO..HI (the count is an immediate, so this is a decision tree)
+template <int LO, int HI>
+__device__ __forceinline__ void wait_vmcnt_tree(int n)
 {
-    if (n >= 4) {
-        if (n >= 6) {
-            if (n >= 8) wait_vmcnt<8>();
-            else if (n == 7) wait_vmcnt<7>();
-            else wait_vmcnt<6>();
-        } else {
-            if (n == 5) wait_vmcnt<5>();
-            else wait_vmcnt<4>();
-        }
+    if constexpr (LO == HI) {
+        wait_vmcnt<LO>();
     } else {
-        if (n >= 2) {
-            if (n == 3) wait_vmcnt<3>();
-            else wait_vmcnt<2>();
-        } else {
-            if (n == 1) wait_vmcnt<1>();
-            else wait_vmcnt<0>();
-        }
+        constexpr int MID = (LO + HI) / 2;
+        if (n <= MID) wait_vmcnt_tree<LO, MID>(n);
+        else wait_vmcnt_tree<MID + 1, HI>(n);
     }
 }
 
@@ -175,29 +172,34 @@ struct TileScan {
     }
 };
 
-template <class C, bool GATEUP>
+template <class C, bool GATEUP, bool TILED>
 struct Stream {
-    static constexpr int FB = C::FB, WF = C::WF, BT = C::BT, BF = C::BF, NSTAGE = C::NSTAGE, NW = C::NW, STAGE = C::STAGE,
-                         KC = C::KC, KS = C::KS, ROWB = C::ROWB, PPR = C::PPR, RPI = C::RPI, NLMAX = C::NLMAX, NWI = C::NWI;
-    static constexpr int NH = NSTAGE > 2 ? NSTAGE - 2 : 1;
+    static constexpr int FB = C::FB, WF = C::WF, BT = C::BT, BF = C::BF, NSW = C::NSW, NST = C::NST, NW = C::NW,
+                         NWW = C::NWW, NWT = C::NWT, WST = C::WST, TST = C::TST, KC = C::KC, KS = C::KS, ROWB = C::ROWB,
+                         PPR = C::PPR, RPI = C::RPI, NLMAX = C::NLMAX, NLW = C::NLW;
+    static constexpr int NH = (NSW > NST ? NSW : NST) > 2 ? (NSW > NST ? NSW : NST) - 2 : 1;
+    static_assert(!TILED || KC == 32, "tiled weights are stored in 32-wide k blocks");
 
     // kernel arguments
     const bf16_t *tok, *w0, *w1;
     bf16_t *out;
     int Kdim, Fdim, nk;
     // LDS
-    unsigned char *ring, *stg;
+    unsigned char *wring, *tring, *stg;
     const int *s_tok;
     const int4 *s_loc;
     // thread position
     int lane, wave, wt, wf, col, half;
     int foff_w, foff_t;  // byte offset in a slot of this lane's k-step-0 fragment of weight block 0 / token block wt
-    // issue side: next chunk to fetch is chunk ikc of item iq, into ring slot islot
+    // Issue side.  A wave fetches one operand only, so that its vmcnt orders one stream: weight waves run
+    // NSW-1 chunks ahead of the MFMAs, token waves NST-1 (token rows mostly come from L2 and need less lead).
+    // The next chunk this wave fetches is chunk ikc of item iq, into slot islot of its ring.
+    bool wrole;
     const bf16_t *src[NLMAX];
-    int nq, iq, ikc, islot, inl, inti;
-    int hist[NH];  // load instructions of this wave in each of the last NSTAGE-2 chunks issued
-    // compute side
-    int cslot;
+    int nq, iq, ikc, islot, inl;
+    int hist[NH];  // load instructions of this wave in each of the last chunks issued (newest last)
+    // compute side: slots of the chunk being multiplied
+    int cslot_w, cslot_t;
 
     __device__ __forceinline__ int4 read_loc(int q) const
     {
@@ -211,38 +213,48 @@ struct Stream {
         if (iq >= nq) { inl = 0; return; }
         const int4 loc = read_loc(iq);
         const int expert = loc.x, rows = loc.z, ft = loc.w;
-        const int g = (rows + 63) >> 6;
-        inti = g * (64 / RPI);
-        const int total = inti + NWI;
-        inl = min(NLMAX, max(0, (total - wave + NW - 1) / NW));
         int ln = lane;
         asm volatile("" : "+v"(ln));  // (recomputed per item rather than kept live)
         const int piece = ln % PPR, rsub = ln / PPR;
-        uint32_t srow[NLMAX];
+        if (wrole) {
+            inl = NLW;
 #pragma unroll
-        for (int i = 0; i < NLMAX; ++i)  // (instructions that fetch weights read an entry too, and ignore it)
-            srow[i] = lds_read_b32(lds_addr(s_tok + iq * BT + min(wave + NW * i, inti - 1) * RPI + rsub));
-#pragma unroll
-        for (int i = 0; i < NLMAX; ++i) lds_wait(srow[i]);
-#pragma unroll
-        for (int i = 0; i < NLMAX; ++i) {
-            const int j = wave + NW * i;
-            if (j < inti) {
-                const int trow = j * RPI + rsub;
-                src[i] = tok + (size_t)srow[i] * Kdim + swz<KC>(trow, piece) * 8;
-            } else {
-                const int row = min(j - inti, NWI - 1) * RPI + rsub;  // (the clamp only keeps unused entries in range)
-                const bf16_t *wbase;
-                int grow;
-                if (GATEUP) {
-                    const int blk = (row >> 5) % FB, wfr = row / (32 * FB);
-                    grow = ft * (BF / 2) + (wfr * (FB / 2) + (blk >> 1)) * 32 + (row & 31);
-                    wbase = (blk & 1) ? w1 : w0;
+            for (int i = 0; i < NLW; ++i) {
+                const int jw = wave + NWW * i;  // covers rows jw*RPI.. of the weight tile
+                if (TILED) {
+                    // 16 rows = one half of a stored 32x32 unit, already in LDS order: lane l copies piece l
+                    const int lb = jw >> 1, blk = lb % FB, wfr = lb / FB;
+                    const bf16_t *wbase = (GATEUP && (blk & 1)) ? w1 : w0;
+                    const int rb = GATEUP ? ft * (BF / 64) + wfr * (FB / 2) + (blk >> 1) : ft * (BF / 32) + lb;
+                    src[i] = wbase + ((size_t)expert * (Fdim / 32) + rb) * (Kdim / 32) * 1024 + (jw & 1) * 512 + ln * 8;
                 } else {
-                    grow = ft * BF + row;
-                    wbase = w0;
+                    const int row = jw * RPI + rsub;
+                    const bf16_t *wbase;
+                    int grow;
+                    if (GATEUP) {
+                        const int blk = (row >> 5) % FB, wfr = row / (32 * FB);
+                        grow = ft * (BF / 2) + (wfr * (FB / 2) + (blk >> 1)) * 32 + (row & 31);
+                        wbase = (blk & 1) ? w1 : w0;
+                    } else {
+                        grow = ft * BF + row;
+                        wbase = w0;
+                    }
+                    src[i] = wbase + ((size_t)expert * Fdim + grow) * Kdim + swz<KC>(row, piece) * 8;
                 }
-                src[i] = wbase + ((size_t)expert * Fdim + grow) * Kdim + swz<KC>(row, piece) * 8;
+            }
+        } else {
+            const int g = (rows + 63) >> 6;
+            inl = C::nlt(g);
+            uint32_t srow[NLMAX];
+#pragma unroll
+            for (int i = 0; i < C::nlt(C::G); ++i)  // (entries past the live groups are read, and never used)
+                srow[i] = lds_read_b32(lds_addr(s_tok + iq * BT + min(wave - NWW + NWT * i, NWT * inl - 1) * RPI + rsub));
+#pragma unroll
+            for (int i = 0; i < C::nlt(C::G); ++i) lds_wait(srow[i]);
+#pragma unroll
+            for (int i = 0; i < C::nlt(C::G); ++i) {
+                const int trow = (wave - NWW + NWT * i) * RPI + rsub;
+                src[i] = tok + (size_t)srow[i] * Kdim + swz<KC>(trow, piece) * 8;
             }
         }
     }
@@ -250,10 +262,10 @@ struct Stream {
     __device__ __forceinline__ void issue_one(int i, int ni)
     {
         if (i < ni) {
-            const int j = wave + NW * i;
-            const int dst = j * 1024 + (j >= inti ? BT * ROWB - inti * 1024 : 0);
-            __builtin_amdgcn_global_load_lds(ZEDA_GLOBAL_PTR(src[i] + (size_t)ikc * KC),
-                                             ZEDA_LDS_PTR(ring + islot * STAGE + dst), 16, 0, 0);
+            const int step = (TILED && wrole) ? 1024 : KC;  // elements from one chunk to the next
+            unsigned char *dst = wrole ? wring + islot * WST + (wave + NWW * i) * 1024
+                                       : tring + islot * TST + (wave - NWW + NWT * i) * 1024;
+            __builtin_amdgcn_global_load_lds(ZEDA_GLOBAL_PTR(src[i] + (size_t)ikc * step), ZEDA_LDS_PTR(dst), 16, 0, 0);
         }
     }
     // bookkeeping after the instructions of one chunk were issued (ni of them; 0 once the stream has ended)
@@ -263,7 +275,7 @@ struct Stream {
         for (int h = 0; h + 1 < NH; ++h) hist[h] = hist[h + 1];
         hist[NH - 1] = ni;
         if (iq < nq) {
-            islot = islot + 1 == NSTAGE ? 0 : islot + 1;
+            islot = islot + 1 == (wrole ? NSW : NST) ? 0 : islot + 1;
             if (++ikc == nk) {
                 ikc = 0;
                 ++iq;
@@ -278,26 +290,25 @@ struct Stream {
         for (int i = 0; i < NLMAX; ++i) issue_one(i, ni);
         issued(ni);
     }
-    // this wave's loads of the oldest chunk in flight have landed
+    // This wave's loads of the oldest chunk in flight have landed: all but the chunks issued after it
+    // (depth - 2 of them, the newest entries of hist) may still be outstanding.
     __device__ __forceinline__ void wait_oldest()
     {
-        if (NSTAGE == 2) {
-            wait_vmcnt<0>();
-        } else {
-            int w = 0;
+        int w = 0;
 #pragma unroll
-            for (int h = 0; h < NH; ++h) w += hist[h];
-            wait_vmcnt_dyn(w);
-        }
+        for (int h = 0; h < NH; ++h)
+            if (NH - h <= (wrole ? NSW - 2 : NST - 2)) w += hist[h];
+        wait_vmcnt_tree<0, C::WMAX>(min(w, C::WMAX));
     }
 
     // Fragments of k step s of the chunk in `slot`: FB weight blocks of this wave column, GA token blocks of this
     // wave row.  Blocks start at multiples of 32 rows, so the piece permutation depends on `col` only and the
     // address is one per-lane term (foff, XOR 32*s) plus block offsets that are immediates.
     template <int GA>
-    __device__ __forceinline__ void load_frags(const unsigned char *slot, int s, bf16x8 (&fa)[FB], bf16x8 (&tb)[GA]) const
+    __device__ __forceinline__ void load_frags(const unsigned char *wslot, const unsigned char *tslot, int s,
+                                               bf16x8 (&fa)[FB], bf16x8 (&tb)[GA]) const
     {
-        const unsigned char *pw = slot + (foff_w ^ (s << 5)), *pt = slot + (foff_t ^ (s << 5));
+        const unsigned char *pw = wslot + (foff_w ^ (s << 5)), *pt = tslot + (foff_t ^ (s << 5));
 #pragma unroll
         for (int b = 0; b < FB; ++b) fa[b] = *reinterpret_cast<const bf16x8 *>(pw + b * 32 * ROWB);
 #pragma unroll
@@ -321,25 +332,25 @@ struct Stream {
         __builtin_amdgcn_s_barrier();
         issue_burst();
         bf16x8 fa[2][FB], tb[2][GA];
-        load_frags<GA>(ring + cslot * STAGE, 0, fa[0], tb[0]);
+        load_frags<GA>(wring + cslot_w * WST, tring + cslot_t * TST, 0, fa[0], tb[0]);
 
         for (int kc = 0; kc < nk; ++kc) {
-            const unsigned char *cur = ring + cslot * STAGE;
-            const int nslot = cslot + 1 == NSTAGE ? 0 : cslot + 1;
+            const unsigned char *cur_w = wring + cslot_w * WST, *cur_t = tring + cslot_t * TST;
+            const int nslot_w = cslot_w + 1 == NSW ? 0 : cslot_w + 1, nslot_t = cslot_t + 1 == NST ? 0 : cslot_t + 1;
             const bool more = kc + 1 < nk;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const int p = s & 1;
                 int ni = 0;
                 if (s < KS - 1) {
-                    load_frags<GA>(cur, s + 1, fa[p ^ 1], tb[p ^ 1]);
+                    load_frags<GA>(cur_w, cur_t, s + 1, fa[p ^ 1], tb[p ^ 1]);
                 } else {
                     // every fragment of this chunk is in registers: nobody needs its slot any more
                     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
                     if (more) {
                         wait_oldest();
                         __builtin_amdgcn_s_barrier();
-                        load_frags<GA>(ring + nslot * STAGE, 0, fa[p ^ 1], tb[p ^ 1]);
+                        load_frags<GA>(wring + nslot_w * WST, tring + nslot_t * TST, 0, fa[p ^ 1], tb[p ^ 1]);
                         ni = inl;
                     }
                 }
@@ -362,7 +373,8 @@ struct Stream {
                 __builtin_amdgcn_sched_barrier(0);
                 if (s == KS - 1 && more) issued(ni);
             }
-            cslot = nslot;
+            cslot_w = nslot_w;
+            cslot_t = nslot_t;
         }
 
         // Epilogue.  acc[a][b][v] is feature 8*(v/4) + 4*half + v%4 of weight block b, token `col` of token
@@ -413,24 +425,24 @@ struct Stream {
     }
 };
 
-template <class C, bool GATEUP, int GA>
+template <class C, bool GATEUP, bool TILED, int GA>
 struct TileDispatch {
-    static __device__ __forceinline__ void run(Stream<C, GATEUP> &st, int g, int expert, int row0, int rows, int ft)
+    static __device__ __forceinline__ void run(Stream<C, GATEUP, TILED> &st, int g, int expert, int row0, int rows, int ft)
     {
         if (g == GA) st.template tile_body<GA>(expert, row0, rows, ft);
-        else TileDispatch<C, GATEUP, GA - 1>::run(st, g, expert, row0, rows, ft);
+        else TileDispatch<C, GATEUP, TILED, GA - 1>::run(st, g, expert, row0, rows, ft);
     }
 };
-template <class C, bool GATEUP>
-struct TileDispatch<C, GATEUP, 0> {
-    static __device__ __forceinline__ void run(Stream<C, GATEUP> &, int, int, int, int, int) {}
+template <class C, bool GATEUP, bool TILED>
+struct TileDispatch<C, GATEUP, TILED, 0> {
+    static __device__ __forceinline__ void run(Stream<C, GATEUP, TILED> &, int, int, int, int, int) {}
 };
 
 // GATEUP: tok = x[T,Kdim], w0 = W_gate[N,Fdim,Kdim], w1 = W_up, out = act[S,Fdim] (Fdim = I, Kdim = H).
 // DOWN:   tok = act[S,Kdim], w0 = W_down[N,Fdim,Kdim], out = y_slot[S,Fdim]        (Fdim = H, Kdim = I).
 // Kdim is a multiple of KC; Fdim a multiple of the feature tile (BF/2 for GATEUP, BF for DOWN).
-// The grid is a multiple of 8 workgroups.
-template <class C, bool GATEUP>
+// TILED: the weights are in the layout pack_weights_kernel writes.  The grid is a multiple of 8 workgroups.
+template <class C, bool GATEUP, bool TILED>
 __global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__restrict__ tok,
                                                               const bf16_t *__restrict__ w0,
                                                               const bf16_t *__restrict__ w1,
@@ -478,26 +490,48 @@ __global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__re
         }
         __syncthreads();
 
-        Stream<C, GATEUP> st;
+        Stream<C, GATEUP, TILED> st;
         st.tok = tok; st.w0 = w0; st.w1 = w1; st.out = out;
         st.Kdim = Kdim; st.Fdim = Fdim; st.nk = Kdim / C::KC;
-        st.ring = lds; st.stg = lds + C::STG_OFF + wave * 2048; st.s_tok = s_tok; st.s_loc = s_loc;
+        st.wring = lds; st.tring = lds + C::TRING_OFF; st.stg = lds + C::STG_OFF + wave * 2048; st.s_tok = s_tok; st.s_loc = s_loc;
         st.lane = lane; st.wave = wave; st.wt = wave / C::WF; st.wf = wave % C::WF; st.col = lane & 31; st.half = lane >> 5;
         st.foff_t = (st.wt * 32 + st.col) * C::ROWB + swz<C::KC>(st.col, st.half) * 16;
-        st.foff_w = (C::BT + st.wf * C::FB * 32 + st.col) * C::ROWB + swz<C::KC>(st.col, st.half) * 16;
-        st.nq = nq; st.iq = 0; st.ikc = 0; st.islot = 0; st.cslot = 0; st.inl = 0; st.inti = 0;
+        st.foff_w = (st.wf * C::FB * 32 + st.col) * C::ROWB + swz<C::KC>(st.col, st.half) * 16;
+        st.wrole = wave < C::NWW;
+        st.nq = nq; st.iq = 0; st.ikc = 0; st.islot = 0; st.cslot_w = 0; st.cslot_t = 0; st.inl = 0;
 #pragma unroll
-        for (int h = 0; h < Stream<C, GATEUP>::NH; ++h) st.hist[h] = 0;
+        for (int h = 0; h < Stream<C, GATEUP, TILED>::NH; ++h) st.hist[h] = 0;
         st.setup_issue_item();
-#pragma unroll
-        for (int c = 0; c < C::NSTAGE - 1; ++c) st.issue_burst();
-        // hist now covers the NSTAGE-2 newest chunks; the oldest one is what the first wait is for
+        for (int c = 0, n = (st.wrole ? C::NSW : C::NST) - 1; c < n; ++c) st.issue_burst();
+        // all slots of this wave's ring but one are in flight; the first wait is for the oldest
 
         for (int q = 0; q < nq; ++q) {
             const int4 loc = st.read_loc(q);
-            TileDispatch<C, GATEUP, C::G>::run(st, (loc.z + 63) >> 6, loc.x, loc.y, loc.z, loc.w);
+            TileDispatch<C, GATEUP, TILED, C::G>::run(st, (loc.z + 63) >> 6, loc.x, loc.y, loc.z, loc.w);
         }
     }
+}
+
+// Tiled weight layout.  A matrix W[F][Kd] (F, Kd multiples of 32) is stored as (F/32) x (Kd/32) units of 2 KiB,
+// unit (rb, kb) at index rb * (Kd/32) + kb, so that the k blocks of one 32-row block follow each other.  A
+// unit holds rows 32rb..32rb+31, columns 32kb..32kb+31 as 32 rows of 64 bytes, the four 16-byte pieces of
+// row r permuted as in the LDS ring (piece p at position p ^ ((r >> 2) & 3)): it is the LDS image of that
+// block, so the GEMM copies it with contiguous 1 KiB loads - which is what lets HBM stream at full rate
+// (row-major weights are fetched as 64- or 128-byte pieces 2*Kd bytes apart).
+// One thread per 16-byte piece of the output; `mats` matrices of F x Kd follow each other.
+__global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ out, int F,
+                                                           int Kd, size_t pieces)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= pieces) return;
+    const int pos = idx & 3, r = (idx >> 2) & 31;
+    const size_t unit = idx >> 7;
+    const int kbs = Kd / 32, units_per_mat = (F / 32) * kbs;
+    const size_t mat = unit / units_per_mat;
+    const int u = (int)(unit - mat * units_per_mat), rb = u / kbs, kb = u - rb * kbs;
+    const int p = pos ^ ((r >> 2) & 3);
+    const bf16x8 v = *reinterpret_cast<const bf16x8 *>(w + (mat * F + rb * 32 + r) * Kd + kb * 32 + p * 8);
+    *reinterpret_cast<bf16x8 *>(out + idx * 8) = v;
 }
 
 }  // namespace zeda

@@ -36,6 +36,8 @@ int launch_gateup(const zeda_layer_desc *d, const void *x, const void *wg, const
                   const int32_t *sorted_slot, void *act, hipStream_t s);
 int launch_down(const zeda_layer_desc *d, const void *act, const void *wd, const int32_t *offsets, void *y_slot,
                 hipStream_t s);
+// row-major -> tiled copy of one expert weight tensor (down: [N,H,I], else [N,I,H])
+int launch_pack_weights(const zeda_layer_desc *d, const void *w, void *out, bool down, hipStream_t s);
 int launch_combine(const zeda_layer_desc *d, const void *y_slot, const int32_t *ids, const float *gates,
                    const int32_t *slot_to_row, void *out, hipStream_t s);
 

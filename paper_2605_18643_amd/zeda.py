@@ -17,16 +17,17 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "lib
 ZEDA_OK, ZEDA_EINVAL, ZEDA_EUNSUPPORTED, ZEDA_EWORKSPACE, ZEDA_EHIP = 0, -1, -2, -3, -4
 ZEDA_F32, ZEDA_BF16 = 0, 1
 GATE_SOFTMAX, GATE_TOPK_NORM, GATE_REAL_RENORM = 0, 1, 2
+WEIGHTS_ROW_MAJOR, WEIGHTS_TILED = 0, 1
 STAGES = ("route", "dispatch", "gateup", "down", "combine")
 
 EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_dispatch_workspace_bytes",
            "zeda_expert_ffn_workspace_bytes", "zeda_workspace_layout", "zeda_route", "zeda_dispatch",
            "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events", "zeda_rmsnorm",
-           "zeda_residual_add")
+           "zeda_residual_add", "zeda_pack_expert_weights")
 
 
 class LayerDesc(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("T", "H", "I", "N", "Z", "K", "dtype", "gate_norm")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "H", "I", "N", "Z", "K", "dtype", "gate_norm", "weight_layout")]
 
 
 class WsLayout(ctypes.Structure):
@@ -75,6 +76,8 @@ def lib() -> ctypes.CDLL:
         L.zeda_rmsnorm.argtypes = [i32, i32, i32, vp, vp, ctypes.c_float, vp, vp]
         L.zeda_residual_add.restype = i32
         L.zeda_residual_add.argtypes = [i32, i32, i32, vp, vp, vp]
+        L.zeda_pack_expert_weights.restype = i32
+        L.zeda_pack_expert_weights.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -83,12 +86,12 @@ def status_string(status: int) -> str:
     return lib().zeda_status_string(int(status)).decode()
 
 
-def make_desc(T, H, I, N, Z, K, dtype, gate_norm=GATE_TOPK_NORM) -> LayerDesc:
+def make_desc(T, H, I, N, Z, K, dtype, gate_norm=GATE_TOPK_NORM, weight_layout=0) -> LayerDesc:
     if isinstance(dtype, torch.dtype):
         dtype = ZEDA_BF16 if dtype == torch.bfloat16 else ZEDA_F32
     elif isinstance(dtype, str):
         dtype = ZEDA_BF16 if dtype == "bf16" else ZEDA_F32
-    return LayerDesc(T, H, I, N, Z, K, int(dtype), int(gate_norm))
+    return LayerDesc(T, H, I, N, Z, K, int(dtype), int(gate_norm), int(weight_layout))
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -177,6 +180,14 @@ def zeda_rmsnorm(x, gamma, eps: float, out, stream=None) -> None:
 def zeda_residual_add(x, y, stream=None) -> None:
     T, H = x.shape
     _check(lib().zeda_residual_add(T, H, _dtype_code(x), _ptr(x), _ptr(y), _stream(stream)), "zeda_residual_add")
+
+
+def zeda_pack_expert_weights(desc, w_gate, w_up, w_down, stream=None):
+    """Tiled copies of the three expert tensors (any of them may be None); allocates the outputs."""
+    outs = [None if w is None else torch.empty_like(w) for w in (w_gate, w_up, w_down)]
+    _check(lib().zeda_pack_expert_weights(ctypes.byref(desc), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(outs[0]),
+                                          _ptr(outs[1]), _ptr(outs[2]), _stream(stream)), "zeda_pack_expert_weights")
+    return tuple(outs)
 
 
 def ws_views(desc: LayerDesc, ws: torch.Tensor):

@@ -13,13 +13,23 @@ from paper_2605_18643_amd import synth, zeda
 BF16_MAX_ABS, BF16_REL_L2, F32_REL = 2e-2, 1e-2, 1e-5
 
 
-def desc_of(w: synth.Workload, gate_norm=zeda.GATE_TOPK_NORM):
-    return zeda.make_desc(w.T, w.H, w.I, w.N, w.Z, w.K, w.dtype, gate_norm)
+def desc_of(w: synth.Workload, gate_norm=zeda.GATE_TOPK_NORM, weight_layout=zeda.WEIGHTS_ROW_MAJOR):
+    return zeda.make_desc(w.T, w.H, w.I, w.N, w.Z, w.K, w.dtype, gate_norm, weight_layout)
 
 
-def forward(w: synth.Workload, L, gate_norm=zeda.GATE_TOPK_NORM):
-    """zeda_moe_forward on device tensors L; returns host copies of the output and of all intermediates."""
-    d = desc_of(w, gate_norm)
+def tiled_layer(w: synth.Workload, L):
+    """The same layer with its expert weights repacked by zeda_pack_expert_weights."""
+    Lt = dict(L)
+    Lt["w_gate"], Lt["w_up"], Lt["w_down"] = zeda.zeda_pack_expert_weights(desc_of(w), L["w_gate"], L["w_up"], L["w_down"])
+    return Lt
+
+
+def forward(w: synth.Workload, L, gate_norm=zeda.GATE_TOPK_NORM, tiled=False):
+    """zeda_moe_forward on device tensors L; returns host copies of the output and of all intermediates.
+    tiled: repack the expert weights first and run the tiled-layout path."""
+    d = desc_of(w, gate_norm, zeda.WEIGHTS_TILED if tiled else zeda.WEIGHTS_ROW_MAJOR)
+    if tiled:
+        L = tiled_layer(w, L)
     ws = torch.empty(zeda.workspace_bytes(d), dtype=torch.uint8, device="cuda")
     out = torch.full((w.T, w.H), float("nan"), dtype=w.torch_dtype, device="cuda")
     nreal = torch.full((1,), -7, dtype=torch.int32, device="cuda")
@@ -60,11 +70,11 @@ def check_float(w, got: np.ndarray, ref: np.ndarray, what: str):
     return rl2, mabs
 
 
-def full_parity(w: synth.Workload, L, gate_norm=zeda.GATE_TOPK_NORM, tokens=None):
+def full_parity(w: synth.Workload, L, gate_norm=zeda.GATE_TOPK_NORM, tokens=None, tiled=False):
     """Whole-layer parity.  With `tokens` (sorted indices) the oracle's expert arithmetic runs on those
     rows only; routing and dispatch are always checked on every token."""
     a = harness.to_arrays(L)
-    res = forward(w, L, gate_norm)
+    res = forward(w, L, gate_norm, tiled)
     ref_ids, ref_gates = orc.route(a["x"], a["w_router"], a["router_bias"], w.N, w.Z, w.K, gate_norm)
     check_routing(w, res, ref_ids, ref_gates)
     off, ss, s2r, R = check_dispatch(w, res, ref_ids)

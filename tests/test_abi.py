@@ -82,6 +82,26 @@ def test_bad_enum_values():
     d = _desc()
     d.gate_norm = 3
     assert zeda.workspace_bytes(d) == 0
+    d = _desc()
+    d.weight_layout = 2
+    assert zeda.workspace_bytes(d) == 0
+
+
+def test_tiled_weights_are_bf16_only():
+    d = _desc(dtype="bf16")
+    d.weight_layout = zeda.WEIGHTS_TILED
+    assert zeda.workspace_bytes(d) > 0
+    d = _desc(dtype="f32")
+    d.weight_layout = zeda.WEIGHTS_TILED
+    assert zeda.workspace_bytes(d) == 0
+    p = ctypes.c_void_p(4096)
+    lib = zeda.lib()
+    assert lib.zeda_moe_forward(ctypes.byref(d), p, p, None, p, p, p, p, None, p, 1 << 40, None) == zeda.ZEDA_EUNSUPPORTED
+    # the packer: fp32 is refused, a lone input or output pointer is an error, all before any launch
+    assert lib.zeda_pack_expert_weights(ctypes.byref(d), p, None, None, ctypes.c_void_p(1 << 30), None, None, None) == zeda.ZEDA_EUNSUPPORTED
+    d = _desc(dtype="bf16")
+    assert lib.zeda_pack_expert_weights(ctypes.byref(d), p, None, None, None, None, None, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_pack_expert_weights(None, p, None, None, p, None, None, None) == zeda.ZEDA_EINVAL
 
 
 def test_pointer_and_workspace_errors_return_before_any_launch():
