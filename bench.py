@@ -27,6 +27,12 @@ from paper_2605_18643_amd import synth, zeda  # noqa: E402
 METRIC = "MoE-layer tokens/s (Qwen3-30B-A3B shape, ~50% zero slots) + MFMA util %"
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+# HBM bytes per launch of the gate/up kernel, from the rocprofv3 counter runs summarised in
+# profiles/ffn_kernels_c2_qwen_prefill_hbm_traffic.txt (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB, both scales read
+# off a plain copy kernel in the same runs).  Counters cannot be read from inside this process, so the figure is
+# only reported for the workload and weight layout it was measured on.
+MEASURED_GATEUP_TRAFFIC_BYTES = {("c2_qwen_prefill", "tiled"): 906.0e6}
+CPU_BASELINE_SECONDS = 12.0      # the oracle keeps making passes over its token sample until this much time has gone by
 
 
 def run_layer(w: synth.Workload, L, steps: int, warmup: int):
@@ -76,7 +82,7 @@ def stack_bench(a) -> int:
     res = {}
     x0 = synth.draw_tokens(w, "cuda")
     for name, static in (("z32", False), ("z0", True)):
-        st = MoeStack(w, a.layers, static=static)
+        st = MoeStack(w, a.layers, static=static, tiled=(a.weights == "tiled"))
         x = x0.clone()
         for _ in range(max(1, a.warmup // 2)):
             st.forward(x.copy_(x0))
@@ -93,7 +99,8 @@ def stack_bench(a) -> int:
            "value": w.T / (res["z32"]["ms_per_pass"] * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
            "warmup": a.warmup, "ms_per_step": res["z32"]["ms_per_pass"], "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-           "config": {"workload": "c5_stack", "layers": a.layers, "T": w.T, "H": w.H, "I": w.I, "N": w.N, "Z": w.Z, "K": w.K},
+           "config": {"workload": "c5_stack", "layers": a.layers, "T": w.T, "H": w.H, "I": w.I, "N": w.N, "Z": w.Z, "K": w.K,
+                      "weight_layout": a.weights},
            "z32": res["z32"], "z0": res["z0"],
            "stack_speedup_vs_z0": res["z0"]["ms_per_pass"] / res["z32"]["ms_per_pass"],
            "expert_flop_reduction": 1.0 - res["z32"]["real_slots"] / max(1, res["z0"]["real_slots"])}
@@ -150,7 +157,8 @@ def main() -> int:
     gu_s, dn_s = stage["gateup"] * 1e-3, stage["down"] * 1e-3
     achieved_gbs = gu_bytes / gu_s / 1e9
     roofline = {"kernel": "ffn_bf16_kernel<gate/up>", "bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": None,
+                "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
+                "traffic": MEASURED_GATEUP_TRAFFIC_BYTES.get((w.name, a.weights if w.dtype == "bf16" else "row_major")),
                 "avg_launch_us": gu_s * 1e6, "algorithmic_bytes": gu_bytes}
     ffn_tflops = (gu_flops + dn_flops) / (gu_s + dn_s) / 1e12
     res = {
@@ -185,12 +193,16 @@ def main() -> int:
         arrays = harness.to_arrays(L_rowmajor)
         n_tok = min(w.T, 4096)
         tok = np.arange(n_tok)
-        t0 = time.perf_counter()
-        ref = harness.oracle_forward(w, arrays, tokens=tok)
-        dt = time.perf_counter() - t0
+        passes, t0 = 0, time.perf_counter()
+        while True:  # whole passes over the sample, about CPU_BASELINE_SECONDS of work in all
+            ref = harness.oracle_forward(w, arrays, tokens=tok)
+            passes += 1
+            dt = time.perf_counter() - t0
+            if dt >= CPU_BASELINE_SECONDS or passes >= 64:
+                break
         got = r["out"][:n_tok].float().cpu().numpy()
-        res["cpu_baseline"] = {"value": n_tok / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
-                               "sample": f"first {n_tok} of {w.T} tokens of {w.name}, one pass, {dt:.1f} s",
+        res["cpu_baseline"] = {"value": passes * n_tok / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"first {n_tok} of {w.T} tokens of {w.name}, {passes} passes, {dt:.1f} s",
                                "gpu_vs_oracle_rel_l2": harness.rel_l2(got, ref["out"])}
     print(json.dumps(res))
     return 0

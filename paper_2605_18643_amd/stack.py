@@ -14,7 +14,8 @@ EPS = 1e-6
 class MoeStack:
     """Per-layer weights drawn by synth (layer l uses seed + l) and the scratch for one pass."""
 
-    def __init__(self, w: synth.Workload, layers: int, device="cuda", static: bool = False):
+    def __init__(self, w: synth.Workload, layers: int, device="cuda", static: bool = False, tiled: bool = False):
+        """tiled: keep the expert weights in the library's tiled layout (packed here, once per layer)."""
         self.w = w if not static else w.with_(Z=0, recipe="plain")
         self.layers = layers
         self.weights: List[Dict[str, Optional[torch.Tensor]]] = []
@@ -23,9 +24,12 @@ class MoeStack:
             wg, wu, wd = synth.draw_experts(w, device, l)
             if static:  # the static top-K layer: router restricted to the normal experts, no bias
                 wr, bias = wr[: w.N].contiguous(), None
+            if tiled:
+                wg, wu, wd = zeda.zeda_pack_expert_weights(zeda.make_desc(w.T, w.H, w.I, w.N, 0, w.K, w.dtype), wg, wu, wd)
             self.weights.append({"w_router": wr, "router_bias": bias, "w_gate": wg, "w_up": wu, "w_down": wd})
         ww = self.w
-        self.desc = zeda.make_desc(ww.T, ww.H, ww.I, ww.N, ww.Z, ww.K, ww.dtype)
+        self.desc = zeda.make_desc(ww.T, ww.H, ww.I, ww.N, ww.Z, ww.K, ww.dtype,
+                                   weight_layout=zeda.WEIGHTS_TILED if tiled else zeda.WEIGHTS_ROW_MAJOR)
         self.ws = torch.empty(zeda.workspace_bytes(self.desc), dtype=torch.uint8, device=device)
         self.xn = torch.empty((ww.T, ww.H), dtype=ww.torch_dtype, device=device)
         self.y = torch.empty((ww.T, ww.H), dtype=ww.torch_dtype, device=device)

@@ -101,3 +101,18 @@ def test_config5_stack_teacher_forced():
         _say(f"layer {l}: {int((~safe).sum())} of {w.T} tokens excluded from the routing comparison; "
              f"sampled output rel-L2 {rl2:.2e} max-abs {mabs:.2e}; r_ZE {1 - nreal[l] / (w.T * w.K):.3f}")
     assert np.isfinite(x.float().cpu().numpy()).all()
+
+
+def test_stack_with_tiled_weights_matches_row_major_bit_for_bit():
+    # same k order and the same accumulation order in both weight layouts: the chained output is identical
+    w = synth.Workload("stack_tiled", T=300, H=256, I=128, N=8, Z=4, K=2, dtype="bf16", seed=91, recipe="zero_bias",
+                       x_std=1.0, w_std=0.05, wr_std=0.05, zero_bias=0.3)
+    _say("stack, tiled against row-major:", w)
+    x0 = synth.draw_tokens(w, "cuda")
+    outs = []
+    for tiled in (False, True):
+        st = MoeStack(w, layers=3, tiled=tiled)
+        outs.append(st.forward(x0.clone()).clone())
+        torch.cuda.synchronize()
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+    assert np.isfinite(outs[0].float().cpu().numpy()).all()
