@@ -2,8 +2,9 @@
 //   out[t,:] = sum over the token's slots on normal experts of g~ * (expert output of that slot).
 // A gather by token: one workgroup per token reads at most K rows of y_slot through slot_to_row and
 // accumulates in fp32 in ascending slot rank, so there are no atomics, the order of additions is
-// fixed, and every load and store is a contiguous 16-byte piece per lane.  A token with no real slot
-// stores exact zeros (its sum is empty).
+// fixed, and every load and store is a contiguous 16-byte piece per lane.  The token's real slots are
+// first compacted (one ballot) so that the row loads can be issued four at a time without a branch per
+// slot.  A token with no real slot stores exact zeros (its sum is empty).
 #include "zeda_internal.h"
 
 namespace zeda {
@@ -29,34 +30,53 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const T *__res
 {
     constexpr int VN = Vec<T>::N;
     typedef typename Vec<T>::type vec_t;
+    // the token's real slots, compacted in ascending slot rank: row in y_slot and routing weight
+    __shared__ int s_row[kMaxK + 4];
+    __shared__ float s_g[kMaxK + 4];
+    __shared__ int s_n;
     const int t = blockIdx.x;
-    // slot j of the token: row in y_slot, or -1 when the slot is on a zero expert (kept in registers)
-    int row[kMaxK];
-    float g[kMaxK];
-#pragma unroll
-    for (int j = 0; j < kMaxK; ++j) {
-        row[j] = -1;
-        g[j] = 0.f;
+    if (threadIdx.x < 64) {
+        const int j = threadIdx.x;
+        int r = -1;
+        float g = 0.f;
         if (j < K) {
             const int s = t * K + j;
             const int e = ids[s];
-            const int r = slot_to_row[s];
-            if (e >= 0 && e < N && r >= 0 && r < rows_cap) {
-                row[j] = r;
-                g[j] = gates[s];
-            }
+            r = slot_to_row[s];
+            g = gates[s];
+            if (!(e >= 0 && e < N && r >= 0 && r < rows_cap)) r = -1;  // a slot on a zero expert (or a bad index)
+        }
+        const unsigned long long real = __ballot(r >= 0);
+        if (r >= 0) {
+            const int pos = __popcll(real & ((1ull << j) - 1ull));
+            s_row[pos] = r;
+            s_g[pos] = g;
+        }
+        const int n = __popcll(real);
+        if (j == 0) s_n = n;
+        if (j < 4) {  // padding of the last group of four: any valid row, weight never used
+            s_row[n + j] = 0;
+            s_g[n + j] = 0.f;
         }
     }
+    __syncthreads();
+    const int n = s_n;
     for (int v = threadIdx.x; v < H / VN; v += kCombineThreads) {
         float acc[VN];
 #pragma unroll
         for (int i = 0; i < VN; ++i) acc[i] = 0.f;
+        // four rows at a time, so that their loads are in flight together; a padded entry is loaded (row 0, or
+        // nothing but readable memory when there are no rows at all) and left out of the sum
+        for (int j0 = 0; j0 < n; j0 += 4) {
+            vec_t y[4];
 #pragma unroll
-        for (int j = 0; j < kMaxK; ++j) {
-            if (row[j] >= 0) {
-                const vec_t y = *reinterpret_cast<const vec_t *>(y_slot + (size_t)row[j] * H + (size_t)v * VN);
+            for (int q = 0; q < 4; ++q) y[q] = *reinterpret_cast<const vec_t *>(y_slot + (size_t)s_row[j0 + q] * H + (size_t)v * VN);
 #pragma unroll
-                for (int i = 0; i < VN; ++i) acc[i] = fmaf(g[j], (float)y[i], acc[i]);
+            for (int q = 0; q < 4; ++q) {
+                const bool use = j0 + q < n;
+                const float g = s_g[j0 + q];
+#pragma unroll
+                for (int i = 0; i < VN; ++i) acc[i] = use ? fmaf(g, (float)y[q][i], acc[i]) : acc[i];
             }
         }
         vec_t o;

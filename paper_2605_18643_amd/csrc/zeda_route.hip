@@ -1,6 +1,8 @@
 // Router of the augmented expert pool (Section 2.1): logits over N normal + Z zero experts, the
 // top-K set with a deterministic lower-index tie-break, and the routing weights (Section 4.3.4 for
 // the normalisation choices).  One fused kernel: projection -> LDS -> wave-level selection.
+#include <limits.h>
+
 #include "zeda_internal.h"
 
 namespace zeda {
@@ -8,140 +10,150 @@ namespace zeda {
 constexpr int kRouteTokens = 32;  // tokens per workgroup of the bf16 kernel (one MFMA column block)
 constexpr int kRouteThreads = 256;
 
-// Wave-wide reductions on the VALU data-parallel-primitive path (no LDS traffic): an inclusive scan inside
-// each row of 16 lanes with row_shr 1, 2, 4, 8 leaves the row result in its last lane; the four row results
-// are then combined in a fixed order.  Every lane returns the same value.
-template <int CTRL>
-__device__ __forceinline__ float dpp_row_shr(float old, float v)
+// Selection runs four tokens per wave, one per row of 16 lanes (the unit of the VALU's data-parallel-primitive
+// cross-lane path), so all reductions stay inside a row and need no LDS traffic and no scalar round trips.
+// row_ror rotates a value inside its row; max/min folded over rotations by 8, 4, 2, 1 leave every lane of the
+// row with the row's result, and since max and min do not depend on the order all lanes agree exactly.
+template <int N>
+__device__ __forceinline__ int dpp_row_ror(int v)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, 0xf, 0xf, false));
+    return __builtin_amdgcn_update_dpp(v, v, 0x120 + N, 0xf, 0xf, false);
 }
-__device__ __forceinline__ float rows_to_all(float v, bool is_max)
+__device__ __forceinline__ float row_max(float v)
 {
+    v = fmaxf(v, __int_as_float(dpp_row_ror<8>(__float_as_int(v))));
+    v = fmaxf(v, __int_as_float(dpp_row_ror<4>(__float_as_int(v))));
+    v = fmaxf(v, __int_as_float(dpp_row_ror<2>(__float_as_int(v))));
+    v = fmaxf(v, __int_as_float(dpp_row_ror<1>(__float_as_int(v))));
+    return v;
+}
+__device__ __forceinline__ int row_min(int v)
+{
+    v = min(v, dpp_row_ror<8>(v));
+    v = min(v, dpp_row_ror<4>(v));
+    v = min(v, dpp_row_ror<2>(v));
+    v = min(v, dpp_row_ror<1>(v));
+    return v;
+}
+// Sum over the row in one fixed order (an inclusive scan with row_shr 1, 2, 4, 8 leaves the total in the row's
+// last lane), handed to every lane of the row, so that all lanes divide by the same number.
+__device__ __forceinline__ float row_sum(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x111, 0xf, 0xf, false));  // lanes without a source add zero
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x112, 0xf, 0xf, false));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x114, 0xf, 0xf, false));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xf, 0xf, false));
     const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 15));
     const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31));
     const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 47));
     const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
-    return is_max ? fmaxf(fmaxf(r0, r1), fmaxf(r2, r3)) : ((r0 + r1) + (r2 + r3));
+    const int r = (threadIdx.x & 63) >> 4;
+    return r == 0 ? r0 : r == 1 ? r1 : r == 2 ? r2 : r3;
 }
-__device__ __forceinline__ float wave_max(float v)
-{
-    v = fmaxf(v, dpp_row_shr<0x111>(v, v));  // lanes without a source keep their own value
-    v = fmaxf(v, dpp_row_shr<0x112>(v, v));
-    v = fmaxf(v, dpp_row_shr<0x114>(v, v));
-    v = fmaxf(v, dpp_row_shr<0x118>(v, v));
-    return rows_to_all(v, true);
-}
+
+// Sum over all 64 lanes in a fixed order, returned to every lane.
 __device__ __forceinline__ float wave_sum(float v)
 {
-    v += dpp_row_shr<0x111>(0.f, v);  // lanes without a source add zero
-    v += dpp_row_shr<0x112>(0.f, v);
-    v += dpp_row_shr<0x114>(0.f, v);
-    v += dpp_row_shr<0x118>(0.f, v);
-    return rows_to_all(v, false);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x111, 0xf, 0xf, false));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x112, 0xf, 0xf, false));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x114, 0xf, 0xf, false));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xf, 0xf, false));
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 15));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 47));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+    return (r0 + r1) + (r2 + r3);
 }
 
-// Selection and gates for NT tokens at once (tokens base, base+4, ... of the workgroup's block, whose
-// fp32 logits are rows of lg in LDS), executed by one wave.  The c-th candidate of a lane is expert
-// lane + 64*c.  One round: the wave maximum, then ballots of the candidates equal to it; the winner is the
-// lowest set bit of the first non-empty ballot, i.e. the lowest expert index among equal logits.  The NT
-// chains are independent and written side by side so that they overlap.
-template <int NT, int NP>
-__device__ __forceinline__ void select_tokens(const float *lg, int LD, int pstride, const float *__restrict__ bias, int base,
-                                              int ntok, int t0, int T, int NE, int N, int K, int gate_norm,
-                                              int32_t *__restrict__ ids, float *__restrict__ gates)
+// Selection and gates for the four tokens tk0..tk0+3 of the workgroup's block (whose fp32 logits are rows of
+// lg in LDS), executed by one wave: token tk0 + r belongs to lane row r, and lane l of the row holds the
+// candidates l, l + 16, ... (NC of them).  One round: the row maximum, then the lowest expert index among the
+// candidates equal to it (ties go to the lower index), which its owner then removes.  Lane j of the row keeps
+// slot j, so lanes 0..K-1 end up with the slots in descending-logit order (K <= 16).
+template <int NC, int NP>
+__device__ __forceinline__ void select_rows(const float *lg, int LD, int pstride, const float *__restrict__ bias, int tk0,
+                                            int ntok, int t0, int T, int NE, int N, int K, int gate_norm,
+                                            int32_t *__restrict__ ids, float *__restrict__ gates)
 {
-    const int lane = threadIdx.x & 63;
-    bool ok[NT];
+    const int lane = threadIdx.x & 63, l16 = lane & 15, tk = tk0 + (lane >> 4);
+    const bool ok = tk < ntok && t0 + tk < T;
+    float cand[NC];
 #pragma unroll
-    for (int i = 0; i < NT; ++i) ok[i] = base + 4 * i < ntok && t0 + base + 4 * i < T;
-    float cand[NT][4], all_max[NT], all_sum[NT], my_logit[NT];
-    int my_id[NT];
+    for (int c = 0; c < NC; ++c) {
+        const int e = l16 + 16 * c;
+        float v = -INFINITY;
+        if (ok && e < NE) {
+            // the NP partial sums over slices of the hidden dimension, added in a fixed order, then the bias
+            v = lg[tk * LD + e];
 #pragma unroll
-    for (int i = 0; i < NT; ++i) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            int e = lane + 64 * c;
-            float v = -INFINITY;
-            if (ok[i] && e < NE) {
-                // the NP partial sums over slices of the hidden dimension, added in a fixed order, then the bias
-                v = lg[(base + 4 * i) * LD + e];
-#pragma unroll
-                for (int q = 1; q < NP; ++q) v += lg[q * pstride + (base + 4 * i) * LD + e];
-                if (bias) v += bias[e];
-            }
-            cand[i][c] = v;
+            for (int q = 1; q < NP; ++q) v += lg[q * pstride + tk * LD + e];
+            if (bias) v += bias[e];
         }
-        my_id[i] = 0;
-        my_logit[i] = -INFINITY;
-        all_sum[i] = 0.f;
+        cand[c] = v;
     }
+    auto local_max = [&]() {
+        float m = cand[0];
 #pragma unroll
-    for (int i = 0; i < NT; ++i)
-        all_max[i] = wave_max(fmaxf(fmaxf(cand[i][0], cand[i][1]), fmaxf(cand[i][2], cand[i][3])));
+        for (int c = 1; c < NC; ++c) m = fmaxf(m, cand[c]);
+        return m;
+    };
+    const float all_max = row_max(local_max());
+    float all_sum = 0.f;
     if (gate_norm == ZEDA_GATE_SOFTMAX) {
+        float sacc = 0.f;
 #pragma unroll
-        for (int i = 0; i < NT; ++i) {
-            float sacc = 0.f;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) sacc += (lane + 64 * c < NE) ? expf(cand[i][c] - all_max[i]) : 0.f;
-            all_sum[i] = wave_sum(sacc);
-        }
+        for (int c = 0; c < NC; ++c) sacc += (l16 + 16 * c < NE) ? expf(cand[c] - all_max) : 0.f;
+        all_sum = row_sum(sacc);
     }
+    int my_id = 0;
+    float my_logit = -INFINITY;
     for (int j = 0; j < K; ++j) {
+        const float m = row_max(local_max());
+        int mine = INT_MAX;
 #pragma unroll
-        for (int i = 0; i < NT; ++i) {
-            const float m = wave_max(fmaxf(fmaxf(cand[i][0], cand[i][1]), fmaxf(cand[i][2], cand[i][3])));
-            int win = -1;
+        for (int c = NC - 1; c >= 0; --c)
+            if (cand[c] == m) mine = l16 + 16 * c;  // descending c: the lowest index survives
+        const int win = row_min(mine);
 #pragma unroll
-            for (int c = 3; c >= 0; --c) {
-                const unsigned long long hit = __ballot(cand[i][c] == m);
-                if (hit) win = 64 * c + (__ffsll((long long)hit) - 1);  // descending c: the lowest index survives
-            }
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (win == lane + 64 * c) cand[i][c] = -INFINITY;
-            if (lane == j) { my_id[i] = win; my_logit[i] = m; }
-        }
+        for (int c = 0; c < NC; ++c)
+            if (win == l16 + 16 * c) cand[c] = -INFINITY;
+        if (l16 == j) { my_id = win; my_logit = m; }
     }
-    // lanes 0..K-1 hold the slots in descending-logit order
-    const bool slot = lane < K;
-#pragma unroll
-    for (int i = 0; i < NT; ++i) {
-        const float ex = slot ? expf(my_logit[i] - all_max[i]) : 0.f;
-        float dn;
-        if (gate_norm == ZEDA_GATE_SOFTMAX) dn = all_sum[i];
-        else if (gate_norm == ZEDA_GATE_TOPK_NORM) dn = wave_sum(ex);
-        else dn = wave_sum((slot && my_id[i] < N) ? ex : 0.f);
-        if (slot && ok[i]) {
-            const size_t o = (size_t)(t0 + base + 4 * i) * K + lane;
-            ids[o] = my_id[i];
-            gates[o] = dn > 0.f ? ex / dn : 0.f;
-        }
+    const bool slot = l16 < K;
+    const float ex = slot ? expf(my_logit - all_max) : 0.f;
+    float dn;
+    if (gate_norm == ZEDA_GATE_SOFTMAX) dn = all_sum;
+    else if (gate_norm == ZEDA_GATE_TOPK_NORM) dn = row_sum(ex);
+    else dn = row_sum((slot && my_id < N) ? ex : 0.f);
+    if (slot && ok) {
+        const size_t o = (size_t)(t0 + tk) * K + l16;
+        ids[o] = my_id;
+        gates[o] = dn > 0.f ? ex / dn : 0.f;
     }
 }
 
-// The tokens tk = wave, wave + 4, ... < ntok of a workgroup, NT at a time.  lg holds NP partial logit
-// tables pstride floats apart.
-template <int NT, int NP>
+// All ntok tokens of a workgroup of NWAVES waves, four per wave at a time.  lg holds NP partial logit tables
+// pstride floats apart.
+template <int NC, int NP, int NWAVES>
 __device__ __forceinline__ void select_block(const float *lg, int LD, int pstride, const float *__restrict__ bias, int ntok,
                                              int t0, int T, int NE, int N, int K, int gate_norm, int32_t *__restrict__ ids,
                                              float *__restrict__ gates)
 {
     const int wave = threadIdx.x >> 6;
-    for (int base = wave; base < ntok; base += 4 * NT)
-        select_tokens<NT, NP>(lg, LD, pstride, bias, base, ntok, t0, T, NE, N, K, gate_norm, ids, gates);
+    for (int tk0 = 4 * wave; tk0 < ntok; tk0 += 4 * NWAVES)
+        select_rows<NC, NP>(lg, LD, pstride, bias, tk0, ntok, t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
 // bf16 router.  A workgroup owns kRouteTokens tokens and all NE experts (NB MFMA row blocks of 32; tokens
-// are the MFMA columns).  x rows and router rows stream through a kRouteStages-deep LDS ring in 64-wide
+// are the MFMA columns).  x rows and router rows stream through an LDS ring (up to six slots) in 64-wide
 // k chunks with global->LDS loads, 128-byte rows whose 16-byte pieces are XOR-permuted by the row index
 // (applied on the global address) so that fragment reads spread over the banks; a counted s_waitcnt and
 // one s_barrier per chunk order the ring.  The four waves split the four 16-wide MFMA steps of every
 // chunk, so each holds a partial sum over a quarter of the hidden dimension; each stores it in an LDS table
 // of its own and the selection adds the four tables in wave order (a fixed order: the logits are
-// reproducible); each wave selects for 8 tokens, four at a time.
-constexpr int kRouteStages = 4;
+// reproducible); each wave selects for 8 tokens, four at a time (one per row of 16 lanes).
+// ring depth: as many slots as fit in LDS, at most six
+constexpr int route_stages(int nb) { return 160 * 1024 / ((kRouteTokens + 32 * nb) * 128) < 6 ? 160 * 1024 / ((kRouteTokens + 32 * nb) * 128) : 6; }
 
 __device__ __forceinline__ int route_swz(int row, int piece) { return piece ^ ((row >> 1) & 7); }
 
@@ -162,6 +174,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
     constexpr int ROWS = kRouteTokens + 32 * NB;  // rows of one ring slot: tokens first, then router rows
     constexpr int STAGE = ROWS * 128;
     constexpr int NL = 1 + NB;                    // wave load instructions (8 rows each) per chunk and wave
+    constexpr int kRouteStages = route_stages(NB);
     static_assert(kRouteTokens == 32 && kRouteThreads == 256, "one token block, four waves");
     static_assert(4 * kRouteTokens * LD * 4 <= kRouteStages * STAGE, "the four partial logit tables reuse the ring");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -229,7 +242,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
 #pragma unroll
         for (int v = 0; v < 16; ++v) mine[col * LD + b * 32 + 8 * (v >> 2) + 4 * half + (v & 3)] = acc[b][v];
     __syncthreads();
-    select_block<4, 4>(lg, LD, kRouteTokens * LD, bias, kRouteTokens, t0, T, NE, N, K, gate_norm, ids, gates);
+    select_block<2 * NB, 4, 4>(lg, LD, kRouteTokens * LD, bias, kRouteTokens, t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
 // fp32 router (plain FMA): a workgroup owns 8 tokens staged in LDS chunk by chunk; a wave walks the
@@ -276,7 +289,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_f32_kernel(const float *_
         }
     }
     __syncthreads();
-    select_block<2, 1>(lg, LD, 0, bias, kRouteF32Tokens, t0, T, NE, N, K, gate_norm, ids, gates);
+    select_block<kMaxExperts / 16, 1, 4>(lg, LD, 0, bias, kRouteF32Tokens, t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
 template <int NB>
@@ -284,7 +297,7 @@ static void launch_route_bf16(const zeda_layer_desc *d, const void *x, const voi
                               float *gates, hipStream_t s)
 {
     dim3 grid(ceil_div(d->T, kRouteTokens));
-    constexpr int lds_bytes = kRouteStages * (kRouteTokens + 32 * NB) * 128;
+    constexpr int lds_bytes = route_stages(NB) * (kRouteTokens + 32 * NB) * 128;
     static bool attr_set = false;  // per instantiation; idempotent, so a race between host threads is harmless
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void *)route_bf16_kernel<NB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
