@@ -17,9 +17,6 @@ constexpr int kWave = 64;
 constexpr int kMaxExperts = 256;  // N + Z
 constexpr int kMaxK = 16;
 
-// dispatch geometry (shared by the size query and the launcher)
-constexpr int kCountSlotsPerBlock = 4096;
-
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -30,8 +27,9 @@ inline size_t elt_size(const zeda_layer_desc *d) { return d->dtype == ZEDA_BF16 
 // stage launchers: arguments are already validated; each returns ZEDA_OK or ZEDA_EHIP
 int launch_route(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
                  float *gates, hipStream_t s);
+// num_real_copy (may be NULL) receives num_real as well
 int launch_dispatch(const zeda_layer_desc *d, const int32_t *ids, int32_t *offsets, int32_t *sorted_slot,
-                    int32_t *slot_to_row, int32_t *num_real, int32_t *block_hist, hipStream_t s);
+                    int32_t *slot_to_row, int32_t *num_real, int32_t *num_real_copy, hipStream_t s);
 int launch_gateup(const zeda_layer_desc *d, const void *x, const void *wg, const void *wu, const int32_t *offsets,
                   const int32_t *sorted_slot, void *act, hipStream_t s);
 int launch_down(const zeda_layer_desc *d, const void *act, const void *wd, const int32_t *offsets, void *y_slot,
