@@ -63,6 +63,12 @@ typedef enum {
  * they are loaded.  bf16 only. */
 typedef enum { ZEDA_WEIGHTS_ROW_MAJOR = 0, ZEDA_WEIGHTS_TILED = 1 } zeda_weight_layout;
 
+/* What a parameter-free expert returns.  ZEDA_EXPERT_ZERO is the method's zero expert (Section 2.1): nothing.
+ * ZEDA_EXPERT_COPY is the copy-expert variant of Appendix B, which returns its input, so the layer output gains
+ * (sum of the routing weights of the token's slots on parameter-free experts) * h.  Either way such a slot
+ * schedules no expert computation. */
+typedef enum { ZEDA_EXPERT_ZERO = 0, ZEDA_EXPERT_COPY = 1 } zeda_free_expert_kind;
+
 typedef struct {
     int32_t T;         /* tokens in this call                      */
     int32_t H;         /* hidden size                              */
@@ -73,6 +79,7 @@ typedef struct {
     int32_t dtype;     /* zeda_dtype of x, weights, out            */
     int32_t gate_norm; /* zeda_gate_norm                           */
     int32_t weight_layout; /* zeda_weight_layout of w_gate, w_up, w_down */
+    int32_t free_expert;   /* zeda_free_expert_kind of experts N..N+Z-1  */
 } zeda_layer_desc;
 
 /* Short name of a status code (host pointer to a static string). */
@@ -115,9 +122,12 @@ int zeda_expert_ffn(const zeda_layer_desc *desc, const void *x, const void *w_ga
 
 /* Eq. 1, the weighted sum back in token order, with a fixed summation order and no atomics:
  *   out[t,:] = sum over j = 0..K-1 with topk_ids[t,j] < N of topk_gates[t,j] * y_slot[slot_to_row[t*K+j], :]
- * accumulated in fp32 in ascending j.  A token with no real slot gets exact zeros. */
+ * accumulated in fp32 in ascending j.  A token with no real slot gets exact zeros.
+ * With desc->free_expert == ZEDA_EXPERT_COPY (Appendix B) the term (sum over j with N <= topk_ids[t,j] < N+Z of
+ * topk_gates[t,j]) * x[t,:] is added last; x[T,H] is the layer input and is only read in that mode (NULL
+ * otherwise is fine). */
 int zeda_combine(const zeda_layer_desc *desc, const void *y_slot, const int32_t *topk_ids, const float *topk_gates,
-                 const int32_t *slot_to_row, void *out /*[T,H]*/, void *stream);
+                 const int32_t *slot_to_row, const void *x, void *out /*[T,H]*/, void *stream);
 
 /* The whole layer: route -> dispatch -> expert FFN -> combine, all on `stream`.
  * num_real_out[0] (device, may be NULL) receives R.  ws: scratch of zeda_workspace_bytes(desc); after

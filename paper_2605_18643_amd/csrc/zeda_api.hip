@@ -12,6 +12,7 @@ int check_desc(const zeda_layer_desc *d)
     if (d->dtype != ZEDA_F32 && d->dtype != ZEDA_BF16) return ZEDA_EINVAL;
     if (d->gate_norm < ZEDA_GATE_SOFTMAX || d->gate_norm > ZEDA_GATE_REAL_RENORM) return ZEDA_EINVAL;
     if (d->weight_layout != ZEDA_WEIGHTS_ROW_MAJOR && d->weight_layout != ZEDA_WEIGHTS_TILED) return ZEDA_EINVAL;
+    if (d->free_expert != ZEDA_EXPERT_ZERO && d->free_expert != ZEDA_EXPERT_COPY) return ZEDA_EINVAL;
     if ((int64_t)d->N + d->Z > kMaxExperts || d->K > kMaxK) return ZEDA_EUNSUPPORTED;
     if ((int64_t)d->T * d->K >= (1 << 24)) return ZEDA_EUNSUPPORTED;
     if (d->dtype == ZEDA_BF16) {
@@ -90,7 +91,7 @@ static int forward_impl(const zeda_layer_desc *desc, const void *x, const void *
     mark(1 + ZEDA_STAGE_GATEUP);
     if ((rc = launch_down(desc, act, w_down, offsets, y_slot, s)) != ZEDA_OK) return rc;
     mark(1 + ZEDA_STAGE_DOWN);
-    if ((rc = launch_combine(desc, y_slot, ids, gates, slot_to_row, out, s)) != ZEDA_OK) return rc;
+    if ((rc = launch_combine(desc, y_slot, ids, gates, slot_to_row, x, out, s)) != ZEDA_OK) return rc;
     mark(1 + ZEDA_STAGE_COMBINE);
     return rc;
 }
@@ -189,16 +190,17 @@ int zeda_expert_ffn(const zeda_layer_desc *desc, const void *x, const void *w_ga
 }
 
 int zeda_combine(const zeda_layer_desc *desc, const void *y_slot, const int32_t *topk_ids, const float *topk_gates,
-                 const int32_t *slot_to_row, void *out, void *stream)
+                 const int32_t *slot_to_row, const void *x, void *out, void *stream)
 {
     int rc = check_desc(desc);
     if (rc != ZEDA_OK) return rc;
-    if (!y_slot || !topk_ids || !topk_gates || !slot_to_row || !out) return ZEDA_EINVAL;
+    const bool copy = desc->free_expert == ZEDA_EXPERT_COPY;
+    if (!y_slot || !topk_ids || !topk_gates || !slot_to_row || !out || (copy && !x)) return ZEDA_EINVAL;
     if (!aligned16(y_slot) || !aligned16(topk_ids) || !aligned16(topk_gates) || !aligned16(slot_to_row) ||
-        !aligned16(out))
+        !aligned16(out) || (copy && !aligned16(x)))
         return ZEDA_EINVAL;
     if (desc->T == 0) return ZEDA_OK;
-    return launch_combine(desc, y_slot, topk_ids, topk_gates, slot_to_row, out, (hipStream_t)stream);
+    return launch_combine(desc, y_slot, topk_ids, topk_gates, slot_to_row, x, out, (hipStream_t)stream);
 }
 
 int zeda_moe_forward(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,

@@ -5,6 +5,8 @@
 // fixed, and every load and store is a contiguous 16-byte piece per lane.  The token's real slots are
 // first compacted (one ballot) so that the row loads can be issued four at a time without a branch per
 // slot.  A token with no real slot stores exact zeros (its sum is empty).
+// Copy-expert variant (Appendix B): a slot on a parameter-free expert contributes g~ * h instead of nothing;
+// those weights are summed in ascending slot rank and the term is added after the real slots.
 #include "zeda_internal.h"
 
 namespace zeda {
@@ -21,12 +23,13 @@ template <> struct Vec<float> {
     typedef f32x4 type;
 };
 
-template <typename T>
+template <typename T, bool COPY>
 __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const T *__restrict__ y_slot,
                                                                   const int32_t *__restrict__ ids,
                                                                   const float *__restrict__ gates,
                                                                   const int32_t *__restrict__ slot_to_row,
-                                                                  T *__restrict__ out, int H, int N, int K, int rows_cap)
+                                                                  const T *__restrict__ x, T *__restrict__ out, int H,
+                                                                  int N, int NE, int K, int rows_cap)
 {
     constexpr int VN = Vec<T>::N;
     typedef typename Vec<T>::type vec_t;
@@ -34,6 +37,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const T *__res
     __shared__ int s_row[kMaxK + 4];
     __shared__ float s_g[kMaxK + 4];
     __shared__ int s_n;
+    __shared__ float s_zg[kMaxK];  // COPY: routing weight of slot j if it is on a parameter-free expert, else 0
     const int t = blockIdx.x;
     if (threadIdx.x < 64) {
         const int j = threadIdx.x;
@@ -44,6 +48,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const T *__res
             const int e = ids[s];
             r = slot_to_row[s];
             g = gates[s];
+            if (COPY) s_zg[j] = (e >= N && e < NE) ? g : 0.f;
             if (!(e >= 0 && e < N && r >= 0 && r < rows_cap)) r = -1;  // a slot on a zero expert (or a bad index)
         }
         const unsigned long long real = __ballot(r >= 0);
@@ -61,6 +66,9 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const T *__res
     }
     __syncthreads();
     const int n = s_n;
+    float gz = 0.f;
+    if (COPY)
+        for (int j = 0; j < K; ++j) gz += s_zg[j];  // ascending slot rank, the same on every thread
     for (int v = threadIdx.x; v < H / VN; v += kCombineThreads) {
         float acc[VN];
 #pragma unroll
@@ -79,6 +87,11 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const T *__res
                 for (int i = 0; i < VN; ++i) acc[i] = use ? fmaf(g, (float)y[q][i], acc[i]) : acc[i];
             }
         }
+        if (COPY) {
+            const vec_t xv = *reinterpret_cast<const vec_t *>(x + (size_t)t * H + (size_t)v * VN);
+#pragma unroll
+            for (int i = 0; i < VN; ++i) acc[i] = fmaf(gz, (float)xv[i], acc[i]);
+        }
         vec_t o;
 #pragma unroll
         for (int i = 0; i < VN; ++i) o[i] = (T)acc[i];
@@ -86,15 +99,24 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const T *__res
     }
 }
 
-int launch_combine(const zeda_layer_desc *d, const void *y_slot, const int32_t *ids, const float *gates,
-                   const int32_t *slot_to_row, void *out, hipStream_t s)
+template <typename T>
+static void launch_combine_t(const zeda_layer_desc *d, const void *y_slot, const int32_t *ids, const float *gates,
+                             const int32_t *slot_to_row, const void *x, void *out, hipStream_t s)
 {
-    if (d->dtype == ZEDA_BF16)
-        combine_kernel<bf16_t><<<d->T, kCombineThreads, 0, s>>>((const bf16_t *)y_slot, ids, gates, slot_to_row,
-                                                               (bf16_t *)out, d->H, d->N, d->K, d->T * d->K);
+    const int S = d->T * d->K, NE = d->N + d->Z;
+    if (d->free_expert == ZEDA_EXPERT_COPY)
+        combine_kernel<T, true><<<d->T, kCombineThreads, 0, s>>>((const T *)y_slot, ids, gates, slot_to_row, (const T *)x,
+                                                                (T *)out, d->H, d->N, NE, d->K, S);
     else
-        combine_kernel<float><<<d->T, kCombineThreads, 0, s>>>((const float *)y_slot, ids, gates, slot_to_row,
-                                                              (float *)out, d->H, d->N, d->K, d->T * d->K);
+        combine_kernel<T, false><<<d->T, kCombineThreads, 0, s>>>((const T *)y_slot, ids, gates, slot_to_row, nullptr,
+                                                                 (T *)out, d->H, d->N, NE, d->K, S);
+}
+
+int launch_combine(const zeda_layer_desc *d, const void *y_slot, const int32_t *ids, const float *gates,
+                   const int32_t *slot_to_row, const void *x, void *out, hipStream_t s)
+{
+    if (d->dtype == ZEDA_BF16) launch_combine_t<bf16_t>(d, y_slot, ids, gates, slot_to_row, x, out, s);
+    else launch_combine_t<float>(d, y_slot, ids, gates, slot_to_row, x, out, s);
     return last_launch_status();
 }
 

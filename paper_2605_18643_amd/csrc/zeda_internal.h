@@ -37,7 +37,7 @@ int launch_down(const zeda_layer_desc *d, const void *act, const void *wd, const
 // row-major -> tiled copy of one expert weight tensor (down: [N,H,I], else [N,I,H])
 int launch_pack_weights(const zeda_layer_desc *d, const void *w, void *out, bool down, hipStream_t s);
 int launch_combine(const zeda_layer_desc *d, const void *y_slot, const int32_t *ids, const float *gates,
-                   const int32_t *slot_to_row, void *out, hipStream_t s);
+                   const int32_t *slot_to_row, const void *x, void *out, hipStream_t s);
 
 inline int last_launch_status() { return hipGetLastError() == hipSuccess ? ZEDA_OK : ZEDA_EHIP; }
 

@@ -18,6 +18,7 @@ ZEDA_OK, ZEDA_EINVAL, ZEDA_EUNSUPPORTED, ZEDA_EWORKSPACE, ZEDA_EHIP = 0, -1, -2,
 ZEDA_F32, ZEDA_BF16 = 0, 1
 GATE_SOFTMAX, GATE_TOPK_NORM, GATE_REAL_RENORM = 0, 1, 2
 WEIGHTS_ROW_MAJOR, WEIGHTS_TILED = 0, 1
+EXPERT_ZERO, EXPERT_COPY = 0, 1
 STAGES = ("route", "dispatch", "gateup", "down", "combine")
 
 EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_dispatch_workspace_bytes",
@@ -27,7 +28,8 @@ EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_dispatch_workspac
 
 
 class LayerDesc(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("T", "H", "I", "N", "Z", "K", "dtype", "gate_norm", "weight_layout")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "H", "I", "N", "Z", "K", "dtype", "gate_norm", "weight_layout",
+                                                 "free_expert")]
 
 
 class WsLayout(ctypes.Structure):
@@ -67,7 +69,7 @@ def lib() -> ctypes.CDLL:
         L.zeda_expert_ffn.restype = i32
         L.zeda_expert_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.zeda_combine.restype = i32
-        L.zeda_combine.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+        L.zeda_combine.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         L.zeda_moe_forward.restype = i32
         L.zeda_moe_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.zeda_moe_forward_events.restype = i32
@@ -86,12 +88,12 @@ def status_string(status: int) -> str:
     return lib().zeda_status_string(int(status)).decode()
 
 
-def make_desc(T, H, I, N, Z, K, dtype, gate_norm=GATE_TOPK_NORM, weight_layout=0) -> LayerDesc:
+def make_desc(T, H, I, N, Z, K, dtype, gate_norm=GATE_TOPK_NORM, weight_layout=0, free_expert=0) -> LayerDesc:
     if isinstance(dtype, torch.dtype):
         dtype = ZEDA_BF16 if dtype == torch.bfloat16 else ZEDA_F32
     elif isinstance(dtype, str):
         dtype = ZEDA_BF16 if dtype == "bf16" else ZEDA_F32
-    return LayerDesc(T, H, I, N, Z, K, int(dtype), int(gate_norm), int(weight_layout))
+    return LayerDesc(T, H, I, N, Z, K, int(dtype), int(gate_norm), int(weight_layout), int(free_expert))
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -145,9 +147,10 @@ def zeda_expert_ffn(desc, x, w_gate, w_up, w_down, expert_offsets, sorted_slot, 
                                  ws.numel() * ws.element_size(), _stream(stream)), "zeda_expert_ffn")
 
 
-def zeda_combine(desc, y_slot, topk_ids, topk_gates, slot_to_row, out, stream=None) -> None:
+def zeda_combine(desc, y_slot, topk_ids, topk_gates, slot_to_row, out, x=None, stream=None) -> None:
+    """x (the layer input) is only needed with desc.free_expert == EXPERT_COPY."""
     _check(lib().zeda_combine(ctypes.byref(desc), _ptr(y_slot), _ptr(topk_ids), _ptr(topk_gates), _ptr(slot_to_row),
-                              _ptr(out), _stream(stream)), "zeda_combine")
+                              _ptr(x), _ptr(out), _stream(stream)), "zeda_combine")
 
 
 def zeda_moe_forward(desc, x, w_router, router_bias, w_gate, w_up, w_down, out, num_real_out, ws,

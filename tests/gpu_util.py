@@ -13,8 +13,9 @@ from paper_2605_18643_amd import synth, zeda
 BF16_MAX_ABS, BF16_REL_L2, F32_REL = 2e-2, 1e-2, 1e-5
 
 
-def desc_of(w: synth.Workload, gate_norm=zeda.GATE_TOPK_NORM, weight_layout=zeda.WEIGHTS_ROW_MAJOR):
-    return zeda.make_desc(w.T, w.H, w.I, w.N, w.Z, w.K, w.dtype, gate_norm, weight_layout)
+def desc_of(w: synth.Workload, gate_norm=zeda.GATE_TOPK_NORM, weight_layout=zeda.WEIGHTS_ROW_MAJOR, copy_expert=False):
+    return zeda.make_desc(w.T, w.H, w.I, w.N, w.Z, w.K, w.dtype, gate_norm, weight_layout,
+                          zeda.EXPERT_COPY if copy_expert else zeda.EXPERT_ZERO)
 
 
 def tiled_layer(w: synth.Workload, L):
@@ -24,10 +25,10 @@ def tiled_layer(w: synth.Workload, L):
     return Lt
 
 
-def forward(w: synth.Workload, L, gate_norm=zeda.GATE_TOPK_NORM, tiled=False):
+def forward(w: synth.Workload, L, gate_norm=zeda.GATE_TOPK_NORM, tiled=False, copy_expert=False):
     """zeda_moe_forward on device tensors L; returns host copies of the output and of all intermediates.
-    tiled: repack the expert weights first and run the tiled-layout path."""
-    d = desc_of(w, gate_norm, zeda.WEIGHTS_TILED if tiled else zeda.WEIGHTS_ROW_MAJOR)
+    tiled: repack the expert weights first and run the tiled-layout path.  copy_expert: Appendix B's variant."""
+    d = desc_of(w, gate_norm, zeda.WEIGHTS_TILED if tiled else zeda.WEIGHTS_ROW_MAJOR, copy_expert)
     if tiled:
         L = tiled_layer(w, L)
     ws = torch.empty(zeda.workspace_bytes(d), dtype=torch.uint8, device="cuda")
@@ -70,23 +71,23 @@ def check_float(w, got: np.ndarray, ref: np.ndarray, what: str):
     return rl2, mabs
 
 
-def full_parity(w: synth.Workload, L, gate_norm=zeda.GATE_TOPK_NORM, tokens=None, tiled=False):
+def full_parity(w: synth.Workload, L, gate_norm=zeda.GATE_TOPK_NORM, tokens=None, tiled=False, copy_expert=False):
     """Whole-layer parity.  With `tokens` (sorted indices) the oracle's expert arithmetic runs on those
     rows only; routing and dispatch are always checked on every token."""
     a = harness.to_arrays(L)
-    res = forward(w, L, gate_norm, tiled)
+    res = forward(w, L, gate_norm, tiled, copy_expert)
     ref_ids, ref_gates = orc.route(a["x"], a["w_router"], a["router_bias"], w.N, w.Z, w.K, gate_norm)
     check_routing(w, res, ref_ids, ref_gates)
     off, ss, s2r, R = check_dispatch(w, res, ref_ids)
-    ref = harness.oracle_forward(w, a, gate_norm, tokens=tokens, want_y_slot=True)
+    ref = harness.oracle_forward(w, a, gate_norm, copy_expert=copy_expert, tokens=tokens, want_y_slot=True)
     tok = np.arange(w.T) if tokens is None else np.asarray(tokens)
     assert np.array_equal(ref["ids"], ref_ids[tok])
     out = res["out"].float().numpy()[tok]
     stats = {"R": R, "r_ze": 1.0 - R / max(1, w.T * w.K), "nonempty": int((np.diff(off) > 0).sum())}
     stats["out"] = check_float(w, out, ref["out"], "out")
-    # all-zero tokens are exact zeros
+    # all-zero tokens are exact zeros (with copy experts they carry the copy term instead)
     allzero = (ref_ids[tok] >= w.N).all(axis=1)
-    assert not out[allzero].any()
+    assert copy_expert or not out[allzero].any()
     # per-slot expert outputs, expert-sorted rows of the sampled tokens
     slots = (tok[:, None] * w.K + np.arange(w.K)[None, :]).ravel()
     rows = s2r[slots]

@@ -85,6 +85,9 @@ def test_bad_enum_values():
     d = _desc()
     d.weight_layout = 2
     assert zeda.workspace_bytes(d) == 0
+    d = _desc()
+    d.free_expert = 2
+    assert zeda.workspace_bytes(d) == 0
 
 
 def test_tiled_weights_are_bf16_only():
@@ -118,8 +121,12 @@ def test_pointer_and_workspace_errors_return_before_any_launch():
     assert lib.zeda_dispatch(dp, ok, ok, ok, ok, ok, ok, zeda.dispatch_workspace_bytes(d) - 1, None) == zeda.ZEDA_EWORKSPACE
     assert lib.zeda_expert_ffn(dp, ok, ok, ok, ok, ok, ok, ok, None, ok, need, None) == zeda.ZEDA_EINVAL
     assert lib.zeda_expert_ffn(dp, ok, ok, ok, ok, ok, ok, ok, ok, ok, zeda.expert_ffn_workspace_bytes(d) - 1, None) == zeda.ZEDA_EWORKSPACE
-    assert lib.zeda_combine(dp, ok, ok, ok, ok, None, None) == zeda.ZEDA_EINVAL
-    assert lib.zeda_combine(dp, ok, ok, ok, odd, ok, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_combine(dp, ok, ok, ok, ok, None, None, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_combine(dp, ok, ok, ok, odd, None, ok, None) == zeda.ZEDA_EINVAL
+    dc = _desc()
+    dc.free_expert = zeda.EXPERT_COPY  # the copy-expert variant reads the layer input
+    assert lib.zeda_combine(ctypes.byref(dc), ok, ok, ok, ok, None, ok, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_combine(ctypes.byref(dc), ok, ok, ok, ok, odd, ok, None) == zeda.ZEDA_EINVAL
     assert lib.zeda_moe_forward(dp, ok, ok, None, ok, ok, ok, ok, None, ok, need - 1, None) == zeda.ZEDA_EWORKSPACE
     assert lib.zeda_moe_forward(dp, ok, ok, None, ok, None, ok, ok, None, ok, need, None) == zeda.ZEDA_EINVAL
     assert lib.zeda_moe_forward_events(dp, ok, ok, None, ok, ok, ok, ok, None, ok, need, None, None) == zeda.ZEDA_EINVAL

@@ -1,0 +1,71 @@
+"""Forward variants the paper describes next to the default layer: the copy expert of Appendix B, and the
+NET baseline of Section 3.1 (the static layer with half the slots: Z = 0, K/2)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import harness, zeda_oracle as orc
+from paper_2605_18643_amd import synth, zeda
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import desc_of, forward, full_parity  # noqa: E402
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+@pytest.mark.parametrize("dtype,seed", [("bf16", 101), ("f32", 102)])
+def test_copy_expert_layer_matches_oracle(dtype, seed):
+    w = synth.Workload("copy", T=500, H=256, I=128, N=10, Z=6, K=4, dtype=dtype, seed=seed, recipe="zero_bias",
+                       x_std=1.0, w_std=0.05, wr_std=0.05, zero_bias=0.3)
+    _say("copy expert", w)
+    L = harness.gapped_layer(w, "cuda")
+    res, st = full_parity(w, L, copy_expert=True)
+    _say(st)
+    # Appendix B: y_copy - y_zero = (sum of the routing weights of the token's parameter-free slots) * h
+    zero = forward(w, L)
+    ids, gates = zero["topk_ids"].numpy(), zero["topk_gates"].numpy().astype(np.float64)
+    gz = np.where(ids >= w.N, gates, 0.0).sum(axis=1)
+    x = synth.to_numpy_f32(L["x"]).astype(np.float64)
+    diff = res["out"].double().numpy() - zero["out"].double().numpy()
+    want = gz[:, None] * x
+    tol = 2e-2 if dtype == "bf16" else 1e-5 * np.abs(want).max()
+    assert np.max(np.abs(diff - want)) <= tol
+    assert (gz > 0).any() and (gz == 0).any()
+
+
+def test_copy_expert_combine_alone_with_all_slots_free():
+    # a token whose slots are all parameter-free returns (sum of its weights) * h, the others the usual sum
+    rng = np.random.default_rng(9)
+    T, H, N, Z, K = 70, 128, 5, 4, 3
+    ids = rng.integers(0, N + Z, size=(T, K)).astype(np.int32)
+    ids[3] = [N, N + 1, N + 3]
+    gates = rng.random((T, K)).astype(np.float32)
+    off, ss, s2r = orc.dispatch(ids, N)
+    R = int(off[N])
+    y = (0.3 * torch.randn(T * K, H, dtype=torch.float32))
+    x = torch.randn(T, H, dtype=torch.float32)
+    d = zeda.make_desc(T, H, 64, N, Z, K, "f32", free_expert=zeda.EXPERT_COPY)
+    out = torch.full((T, H), float("nan"), dtype=torch.float32, device="cuda")
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    zeda.zeda_combine(d, y.cuda(), dev(ids), dev(gates), dev(s2r), out, x=x.cuda())
+    torch.cuda.synchronize()
+    ref = orc.combine(y.numpy().astype(np.float64)[:max(R, 1)], ids, gates.astype(np.float64), s2r, N)
+    ref += np.where(ids >= N, gates.astype(np.float64), 0.0).sum(axis=1)[:, None] * x.numpy().astype(np.float64)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - ref)) <= 1e-5 * np.abs(ref).max()
+    np.testing.assert_allclose(got[3], gates[3].astype(np.float64).sum() * x.numpy()[3], rtol=1e-5, atol=1e-6)
+    with pytest.raises(zeda.ZedaError):
+        zeda.zeda_combine(d, y.cuda(), dev(ids), dev(gates), dev(s2r), out)  # the layer input is required in this mode
+
+
+def test_net_baseline_static_layer_with_half_the_slots():
+    # Section 3.1's NET: no parameter-free experts, K/2 slots per token - the same path at Z = 0
+    w = synth.CONFIGS["c2_qwen_prefill"].with_(Z=0, K=4, recipe="plain", T=768)
+    _say("NET", w)
+    L = harness.gapped_layer(w, "cuda")
+    res, st = full_parity(w, L, tokens=np.arange(0, w.T, 3))
+    _say(st)
+    assert st["R"] == w.T * w.K and st["r_ze"] == 0.0
