@@ -116,6 +116,7 @@ def main() -> int:
     ap.add_argument("--workload", default="c2_qwen_prefill", choices=sorted(synth.CONFIGS) + ["c5_stack"],
                     help="c5_stack: the 48-layer chain (RMSNorm + residual, no attention) with and without zero experts")
     ap.add_argument("--layers", type=int, default=48)
+    ap.add_argument("--tokens", type=int, default=0, help="override T of the workload (sequence-length sweeps)")
     ap.add_argument("--weights", default="tiled", choices=["tiled", "row_major"],
                     help="storage of the expert weights: packed once into the library's tiled layout (default), or row-major")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -133,6 +134,8 @@ def main() -> int:
         return stack_bench(a)
 
     w = synth.CONFIGS[a.workload]
+    if a.tokens > 0:
+        w = w.with_(T=a.tokens)
     L = synth.make_layer(w, "cuda")
     L_rowmajor = L
     if a.weights == "tiled" and w.dtype == "bf16":

@@ -186,6 +186,9 @@ class Workload:
 # the mean number of zero-expert slots per token is 4.0 +- 0.05 of K=8 at the
 # Qwen3-shaped layer (N=128, Z=32, H=2048, x~N(0,1), W_r~N(0,0.02^2)).
 QWEN_ZERO_BIAS = 0.6468
+# the same calibration for N=128, Z=64, K=8 and for N=64, Z=32, K=4 (H=2048 both): half of the slots
+NZ64_ZERO_BIAS = 0.2991
+GLM_LIKE_ZERO_BIAS = 0.3092
 
 CONFIGS: Dict[str, Workload] = {
     # BASELINE config 1: tiny fp32 layer, no bias, seed 0.
@@ -203,6 +206,16 @@ CONFIGS: Dict[str, Workload] = {
     # BASELINE config 5: one layer of the 48-layer stack (T=8192); layer l uses seed 4000 + l.
     "c5_stack_layer": Workload("c5_stack_layer", T=8192, H=2048, I=768, N=128, Z=32, K=8, dtype="bf16",
                                seed=4000, recipe="zero_bias", zero_bias=QWEN_ZERO_BIAS),
+    # Further workloads (not in the benchmark spec).  The paper's own zero-expert count on the Qwen3 shape (App. D
+    # Table 12: N_Z = 64), prefill and its decode concurrency of 32 ...
+    "n1_qwen_nz64_prefill": Workload("n1_qwen_nz64_prefill", T=4096, H=2048, I=768, N=128, Z=64, K=8, dtype="bf16",
+                                     seed=11, recipe="zero_bias", zero_bias=NZ64_ZERO_BIAS),
+    "n1_qwen_nz64_decode32": Workload("n1_qwen_nz64_decode32", T=32, H=2048, I=768, N=128, Z=64, K=8, dtype="bf16",
+                                      seed=12, recipe="zero_bias", zero_bias=NZ64_ZERO_BIAS),
+    # ... and a layer with the router of the paper's second model (Section 3.1: N = 64, K = 4, N_Z = 32).  Its
+    # hidden sizes are not given in the paper: H and I here are this build's choice.
+    "n1_glm_like_prefill": Workload("n1_glm_like_prefill", T=4096, H=2048, I=1536, N=64, Z=32, K=4, dtype="bf16",
+                                    seed=13, recipe="zero_bias", zero_bias=GLM_LIKE_ZERO_BIAS),
 }
 
 

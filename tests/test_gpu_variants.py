@@ -69,3 +69,29 @@ def test_net_baseline_static_layer_with_half_the_slots():
     res, st = full_parity(w, L, tokens=np.arange(0, w.T, 3))
     _say(st)
     assert st["R"] == w.T * w.K and st["r_ze"] == 0.0
+
+
+# Further workloads: the paper's own zero-expert count on the Qwen3 shape (N_Z = 64, so 192 router rows), its
+# decode concurrency of 32, and a layer with the router of its second model (N = 64, K = 4, N_Z = 32).
+@pytest.mark.parametrize("name,sample", [("n1_qwen_nz64_prefill", 256), ("n1_qwen_nz64_decode32", None),
+                                         ("n1_glm_like_prefill", 256)])
+def test_further_workloads(name, sample):
+    w = synth.CONFIGS[name]
+    _say(name, w)
+    L = harness.gapped_layer(w, "cuda")
+    tokens = None if sample is None else np.sort(np.random.default_rng(1).choice(w.T, size=sample, replace=False))
+    res, st = full_parity(w, L, tokens=tokens, tiled=True)
+    _say(st)
+    if w.T >= 1024:
+        assert abs(st["r_ze"] - 0.5) < 0.03
+
+
+@pytest.mark.parametrize("T", [2048, 8192])
+def test_sequence_length_sweep_ends(T):
+    # the paper varies the sequence length between 2k and 8k: both ends on the Qwen3 layer, sampled tokens
+    w = synth.CONFIGS["c2_qwen_prefill"].with_(T=T, seed=21)
+    _say("T sweep", w)
+    L = harness.gapped_layer(w, "cuda")
+    tokens = np.sort(np.random.default_rng(2).choice(w.T, size=128, replace=False))
+    res, st = full_parity(w, L, tokens=tokens, tiled=True)
+    _say(st)
