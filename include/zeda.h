@@ -88,6 +88,7 @@ const char *zeda_status_string(int status);
 /* Host-only size queries; 0 if the descriptor is invalid or unsupported.
  * zeda_workspace_bytes covers zeda_moe_forward and is >= the other two. */
 size_t zeda_workspace_bytes(const zeda_layer_desc *desc);
+size_t zeda_route_workspace_bytes(const zeda_layer_desc *desc); /* may be 0: no scratch needed for this shape */
 size_t zeda_dispatch_workspace_bytes(const zeda_layer_desc *desc);
 size_t zeda_expert_ffn_workspace_bytes(const zeda_layer_desc *desc);
 
@@ -95,9 +96,13 @@ size_t zeda_expert_ffn_workspace_bytes(const zeda_layer_desc *desc);
  *   logit[t,e] = <x[t,:], w_router[e,:]> (+ router_bias[e]),  e in [0, N+Z);
  *   topk_ids[t,0..K) = the K largest logits of token t in descending order (fp32 compare, ties to
  *   the lower index); topk_gates[t,j] = routing weight of that slot under desc->gate_norm.
- * router_bias[N+Z] (fp32) may be NULL (the paper's router has none).  T = 0 is a no-op. */
+ * router_bias[N+Z] (fp32) may be NULL (the paper's router has none).  T = 0 is a no-op.
+ * ws: scratch of zeda_route_workspace_bytes(desc), or NULL.  With scratch, a layer with few tokens spreads the
+ * projection of a token block over several workgroups (each a slice of the hidden dimension, summed in a fixed
+ * order); without it one workgroup does a block alone.  The ids are the same either way; logits may differ in
+ * the last bit between the two. */
 int zeda_route(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,
-               int32_t *topk_ids /*[T,K]*/, float *topk_gates /*[T,K]*/, void *stream);
+               int32_t *topk_ids /*[T,K]*/, float *topk_gates /*[T,K]*/, void *ws, size_t ws_bytes, void *stream);
 
 /* Zero-slot removal and expert-sorted order (Section 2.1: zero experts contribute no computation).
  * A slot s = t*K+j is real iff topk_ids[s] < N.  The real slots are listed grouped by expert, and
@@ -165,7 +170,8 @@ int zeda_pack_expert_weights(const zeda_layer_desc *desc, const void *w_gate, co
 
 /* Byte offsets inside the forward workspace (host-only).  Returns ZEDA_OK or an error. */
 typedef struct {
-    size_t topk_ids, topk_gates, expert_offsets, sorted_slot, slot_to_row, num_real, dispatch_ws, act, y_slot, total;
+    size_t topk_ids, topk_gates, expert_offsets, sorted_slot, slot_to_row, num_real, dispatch_ws, act, y_slot, route_ws,
+        total;
 } zeda_ws_layout;
 int zeda_workspace_layout(const zeda_layer_desc *desc, zeda_ws_layout *layout /* host */);
 

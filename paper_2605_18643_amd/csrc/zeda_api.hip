@@ -48,6 +48,7 @@ static void layout_of(const zeda_layer_desc *d, zeda_ws_layout *L)
     L->dispatch_ws = take(dispatch_ws_bytes(d));
     L->act = take(act_bytes(d));
     L->y_slot = take(S * d->H * elt_size(d));
+    L->route_ws = take(route_ws_bytes(d));
     L->total = o;
 }
 
@@ -74,6 +75,7 @@ static int forward_impl(const zeda_layer_desc *desc, const void *x, const void *
     int32_t *num_real = (int32_t *)(w + L.num_real);
     void *act = w + L.act;
     void *y_slot = w + L.y_slot;
+    float *route_ws = route_ws_bytes(desc) ? (float *)(w + L.route_ws) : nullptr;
 
     auto mark = [&](int i) {
         if (events && hipEventRecord((hipEvent_t)events[i], s) != hipSuccess) rc = ZEDA_EHIP;
@@ -83,7 +85,7 @@ static int forward_impl(const zeda_layer_desc *desc, const void *x, const void *
         for (int i = 1; i <= ZEDA_NUM_STAGES; ++i) mark(i);
         return rc;
     }
-    if ((rc = launch_route(desc, x, w_router, router_bias, ids, gates, s)) != ZEDA_OK) return rc;
+    if ((rc = launch_route(desc, x, w_router, router_bias, ids, gates, route_ws, s)) != ZEDA_OK) return rc;
     mark(1 + ZEDA_STAGE_ROUTE);
     if ((rc = launch_dispatch(desc, ids, offsets, sorted_slot, slot_to_row, num_real, num_real_out, s)) != ZEDA_OK) return rc;
     mark(1 + ZEDA_STAGE_DISPATCH);
@@ -143,17 +145,25 @@ int zeda_workspace_layout(const zeda_layer_desc *desc, zeda_ws_layout *layout)
     return ZEDA_OK;
 }
 
+size_t zeda_route_workspace_bytes(const zeda_layer_desc *desc)
+{
+    if (check_desc(desc) != ZEDA_OK) return 0;
+    return route_ws_bytes(desc);
+}
+
 int zeda_route(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,
-               int32_t *topk_ids, float *topk_gates, void *stream)
+               int32_t *topk_ids, float *topk_gates, void *ws, size_t ws_bytes, void *stream)
 {
     int rc = check_desc(desc);
     if (rc != ZEDA_OK) return rc;
     if (!x || !w_router || !topk_ids || !topk_gates) return ZEDA_EINVAL;
     if (!aligned16(x) || !aligned16(w_router) || !aligned16(topk_ids) || !aligned16(topk_gates) ||
-        (router_bias && !aligned16(router_bias)))
+        (router_bias && !aligned16(router_bias)) || (ws && !aligned16(ws)))
         return ZEDA_EINVAL;
+    if (ws && ws_bytes < route_ws_bytes(desc)) return ZEDA_EWORKSPACE;
     if (desc->T == 0) return ZEDA_OK;
-    return launch_route(desc, x, w_router, router_bias, topk_ids, topk_gates, (hipStream_t)stream);
+    float *partial = (ws && route_ws_bytes(desc)) ? (float *)ws : nullptr;
+    return launch_route(desc, x, w_router, router_bias, topk_ids, topk_gates, partial, (hipStream_t)stream);
 }
 
 int zeda_dispatch(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t *expert_offsets, int32_t *sorted_slot,

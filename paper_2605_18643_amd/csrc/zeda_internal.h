@@ -25,8 +25,10 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t elt_size(const zeda_layer_desc *d) { return d->dtype == ZEDA_BF16 ? 2 : 4; }
 
 // stage launchers: arguments are already validated; each returns ZEDA_OK or ZEDA_EHIP
+// partial: scratch of route_ws_bytes(d) for the split-k launch, or NULL (one kernel, no scratch)
 int launch_route(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
-                 float *gates, hipStream_t s);
+                 float *gates, float *partial, hipStream_t s);
+size_t route_ws_bytes(const zeda_layer_desc *d);
 // num_real_copy (may be NULL) receives num_real as well
 int launch_dispatch(const zeda_layer_desc *d, const int32_t *ids, int32_t *offsets, int32_t *sorted_slot,
                     int32_t *slot_to_row, int32_t *num_real, int32_t *num_real_copy, hipStream_t s);

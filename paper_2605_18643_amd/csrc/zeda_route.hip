@@ -71,7 +71,7 @@ __device__ __forceinline__ float wave_sum(float v)
 // candidates equal to it (ties go to the lower index), which its owner then removes.  Lane j of the row keeps
 // slot j, so lanes 0..K-1 end up with the slots in descending-logit order (K <= 16).
 template <int NC, int NP>
-__device__ __forceinline__ void select_rows(const float *lg, int LD, int pstride, const float *__restrict__ bias, int tk0,
+__device__ __forceinline__ void select_rows(const float *lg, int LD, int pstride, int np_rt, const float *__restrict__ bias, int tk0,
                                             int ntok, int t0, int T, int NE, int N, int K, int gate_norm,
                                             int32_t *__restrict__ ids, float *__restrict__ gates)
 {
@@ -86,7 +86,7 @@ __device__ __forceinline__ void select_rows(const float *lg, int LD, int pstride
             // the NP partial sums over slices of the hidden dimension, added in a fixed order, then the bias
             v = lg[tk * LD + e];
 #pragma unroll
-            for (int q = 1; q < NP; ++q) v += lg[q * pstride + tk * LD + e];
+            for (int q = 1; q < NP; ++q) v += lg[(size_t)q * pstride + tk * LD + e];
             if (bias) v += bias[e];
         }
         cand[c] = v;
@@ -135,13 +135,13 @@ __device__ __forceinline__ void select_rows(const float *lg, int LD, int pstride
 // All ntok tokens of a workgroup of NWAVES waves, four per wave at a time.  lg holds NP partial logit tables
 // pstride floats apart.
 template <int NC, int NP, int NWAVES>
-__device__ __forceinline__ void select_block(const float *lg, int LD, int pstride, const float *__restrict__ bias, int ntok,
+__device__ __forceinline__ void select_block(const float *lg, int LD, int pstride, int np_rt, const float *__restrict__ bias, int ntok,
                                              int t0, int T, int NE, int N, int K, int gate_norm, int32_t *__restrict__ ids,
                                              float *__restrict__ gates)
 {
     const int wave = threadIdx.x >> 6;
     for (int tk0 = 4 * wave; tk0 < ntok; tk0 += 4 * NWAVES)
-        select_rows<NC, NP>(lg, LD, pstride, bias, tk0, ntok, t0, T, NE, N, K, gate_norm, ids, gates);
+        select_rows<NC, NP>(lg, LD, pstride, np_rt, bias, tk0, ntok, t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
 // bf16 router.  A workgroup owns kRouteTokens tokens and all NE experts (NB MFMA row blocks of 32; tokens
@@ -168,7 +168,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
                                                                    const bf16_t *__restrict__ wr,
                                                                    const float *__restrict__ bias, int T, int H, int N,
                                                                    int NE, int K, int gate_norm,
-                                                                   int32_t *__restrict__ ids, float *__restrict__ gates)
+                                                                   int32_t *__restrict__ ids, float *__restrict__ gates,
+                                                                   float *__restrict__ partial, int Tpad)
 {
     constexpr int LD = NB * 32 + 1;
     constexpr int ROWS = kRouteTokens + 32 * NB;  // rows of one ring slot: tokens first, then router rows
@@ -196,7 +197,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
     // k chunk of every row sits on a single L2 channel: workgroups walking the chunks in the same order
     // would queue on that channel.  Each starts at a different chunk instead (the sum over k does not
     // depend on the order; the order is fixed per workgroup, so results stay reproducible).
-    const int nk = H / 64;
+    // gridDim.y workgroups share a token block: each takes a contiguous slice of the hidden dimension
+    const int nk = H / 64 / gridDim.y, k0 = blockIdx.y * nk;
     const int rot = (int)((blockIdx.x * 5u) % (unsigned)nk);
     auto issue = [&](int chunk) {
         unsigned char *slot = lds + (chunk % kRouteStages) * STAGE;
@@ -204,7 +206,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
         if (kc >= nk) kc -= nk;
 #pragma unroll
         for (int i = 0; i < NL; ++i)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[i] + (size_t)kc * 64),
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[i] + (size_t)(k0 + kc) * 64),
                                              (__attribute__((address_space(3))) void *)(slot + (wave + 4 * i) * 1024), 16, 0, 0);
     };
 
@@ -242,7 +244,34 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
 #pragma unroll
         for (int v = 0; v < 16; ++v) mine[col * LD + b * 32 + 8 * (v >> 2) + 4 * half + (v & 3)] = acc[b][v];
     __syncthreads();
-    select_block<2 * NB, 4, 4>(lg, LD, kRouteTokens * LD, bias, kRouteTokens, t0, T, NE, N, K, gate_norm, ids, gates);
+    if (partial == nullptr) {
+        select_block<2 * NB, 4, 4>(lg, LD, kRouteTokens * LD, 4, bias, kRouteTokens, t0, T, NE, N, K, gate_norm, ids, gates);
+    } else {
+        // split-k launch: this workgroup's sums over its slice (the four wave tables added in wave order) go to
+        // partial[blockIdx.y][token][expert]; route_select_kernel adds the slices in order and selects
+        float *dst = partial + ((size_t)blockIdx.y * Tpad + t0) * (NB * 32);
+        for (int i = tid; i < kRouteTokens * NB * 32; i += kRouteThreads) {
+            const int tk = i / (NB * 32), e = i - tk * (NB * 32);
+            float v = lg[tk * LD + e];
+#pragma unroll
+            for (int q = 1; q < 4; ++q) v += lg[q * kRouteTokens * LD + tk * LD + e];
+            dst[i] = v;
+        }
+    }
+}
+
+// Second step of a split-k launch: 16 tokens per workgroup, four per wave, logits read from the partial tables.
+constexpr int kSelectTokens = 16;
+template <int NB, int NSPLIT>
+__global__ __launch_bounds__(kRouteThreads) void route_select_kernel(const float *__restrict__ partial, int Tpad,
+                                                                     const float *__restrict__ bias, int T, int N, int NE,
+                                                                     int K, int gate_norm, int32_t *__restrict__ ids,
+                                                                     float *__restrict__ gates)
+{
+    const int t0 = blockIdx.x * kSelectTokens;
+    // (the number of slices is a template parameter so that all loads of a lane's candidates are issued together)
+    select_block<2 * NB, NSPLIT, 4>(partial + (size_t)t0 * (NB * 32), NB * 32, Tpad * NB * 32, NSPLIT, bias, kSelectTokens,
+                                    t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
 // fp32 router (plain FMA): a workgroup owns 8 tokens staged in LDS chunk by chunk; a wave walks the
@@ -289,38 +318,67 @@ __global__ __launch_bounds__(kRouteThreads) void route_f32_kernel(const float *_
         }
     }
     __syncthreads();
-    select_block<kMaxExperts / 16, 1, 4>(lg, LD, 0, bias, kRouteF32Tokens, t0, T, NE, N, K, gate_norm, ids, gates);
+    select_block<kMaxExperts / 16, 1, 4>(lg, LD, 0, 1, bias, kRouteF32Tokens, t0, T, NE, N, K, gate_norm, ids, gates);
+}
+
+// How many workgroups share a token block (bf16 with scratch): enough to fill the device when there are few
+// token blocks, never more than eight, and the hidden dimension must split into whole 64-wide chunks.
+int route_ksplit(const zeda_layer_desc *d)
+{
+    if (d->dtype != ZEDA_BF16) return 1;
+    const int blocks = ceil_div(d->T, kRouteTokens), chunks = d->H / 64;
+    int c = 1;
+    while (c < 8 && blocks * c < 256 && chunks % (2 * c) == 0) c *= 2;
+    return c;
+}
+
+size_t route_ws_bytes(const zeda_layer_desc *d)
+{
+    const int c = route_ksplit(d);
+    if (c == 1) return 0;
+    const size_t Tpad = (size_t)ceil_div(d->T, kRouteTokens) * kRouteTokens;
+    return (size_t)c * Tpad * ceil_div(d->N + d->Z, 32) * 32 * sizeof(float);
 }
 
 template <int NB>
 static void launch_route_bf16(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
-                              float *gates, hipStream_t s)
+                              float *gates, float *partial, hipStream_t s)
 {
-    dim3 grid(ceil_div(d->T, kRouteTokens));
+    const int blocks = ceil_div(d->T, kRouteTokens), Tpad = blocks * kRouteTokens;
+    const int c = partial ? route_ksplit(d) : 1;
     constexpr int lds_bytes = route_stages(NB) * (kRouteTokens + 32 * NB) * 128;
     static bool attr_set = false;  // per instantiation; idempotent, so a race between host threads is harmless
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void *)route_bf16_kernel<NB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         attr_set = true;
     }
-    route_bf16_kernel<NB><<<grid, kRouteThreads, lds_bytes, s>>>((const bf16_t *)x, (const bf16_t *)wr, bias, d->T, d->H, d->N,
-                                                         d->N + d->Z, d->K, d->gate_norm, ids, gates);
+    route_bf16_kernel<NB><<<dim3(blocks, c), kRouteThreads, lds_bytes, s>>>(
+        (const bf16_t *)x, (const bf16_t *)wr, bias, d->T, d->H, d->N, d->N + d->Z, d->K, d->gate_norm, ids, gates,
+        c > 1 ? partial : nullptr, Tpad);
+    const dim3 sgrid(ceil_div(d->T, kSelectTokens));
+    const int NE = d->N + d->Z;
+    if (c == 2)
+        route_select_kernel<NB, 2><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates);
+    else if (c == 4)
+        route_select_kernel<NB, 4><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates);
+    else if (c == 8)
+        route_select_kernel<NB, 8><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates);
 }
 
 int launch_route(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
-                 float *gates, hipStream_t s)
+                 float *gates, float *partial, hipStream_t s)
 {
     const int NE = d->N + d->Z;
     if (d->dtype == ZEDA_BF16) {
         switch (ceil_div(NE, 32)) {
-            case 1: launch_route_bf16<1>(d, x, wr, bias, ids, gates, s); break;
-            case 2: launch_route_bf16<2>(d, x, wr, bias, ids, gates, s); break;
-            case 3: launch_route_bf16<3>(d, x, wr, bias, ids, gates, s); break;
-            case 4: launch_route_bf16<4>(d, x, wr, bias, ids, gates, s); break;
-            case 5: launch_route_bf16<5>(d, x, wr, bias, ids, gates, s); break;
-            case 6: launch_route_bf16<6>(d, x, wr, bias, ids, gates, s); break;
-            case 7: launch_route_bf16<7>(d, x, wr, bias, ids, gates, s); break;
-            default: launch_route_bf16<8>(d, x, wr, bias, ids, gates, s); break;
+            case 1: launch_route_bf16<1>(d, x, wr, bias, ids, gates, partial, s); break;
+            case 2: launch_route_bf16<2>(d, x, wr, bias, ids, gates, partial, s); break;
+            case 3: launch_route_bf16<3>(d, x, wr, bias, ids, gates, partial, s); break;
+            case 4: launch_route_bf16<4>(d, x, wr, bias, ids, gates, partial, s); break;
+            case 5: launch_route_bf16<5>(d, x, wr, bias, ids, gates, partial, s); break;
+            case 6: launch_route_bf16<6>(d, x, wr, bias, ids, gates, partial, s); break;
+            case 7: launch_route_bf16<7>(d, x, wr, bias, ids, gates, partial, s); break;
+            default: launch_route_bf16<8>(d, x, wr, bias, ids, gates, partial, s); break;
         }
     } else {
         dim3 grid(ceil_div(d->T, kRouteF32Tokens));

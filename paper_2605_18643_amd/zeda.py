@@ -21,7 +21,7 @@ WEIGHTS_ROW_MAJOR, WEIGHTS_TILED = 0, 1
 EXPERT_ZERO, EXPERT_COPY = 0, 1
 STAGES = ("route", "dispatch", "gateup", "down", "combine")
 
-EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_dispatch_workspace_bytes",
+EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_route_workspace_bytes", "zeda_dispatch_workspace_bytes",
            "zeda_expert_ffn_workspace_bytes", "zeda_workspace_layout", "zeda_route", "zeda_dispatch",
            "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events", "zeda_rmsnorm",
            "zeda_residual_add", "zeda_pack_expert_weights")
@@ -34,7 +34,8 @@ class LayerDesc(ctypes.Structure):
 
 class WsLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in ("topk_ids", "topk_gates", "expert_offsets", "sorted_slot",
-                                               "slot_to_row", "num_real", "dispatch_ws", "act", "y_slot", "total")]
+                                               "slot_to_row", "num_real", "dispatch_ws", "act", "y_slot", "route_ws",
+                                               "total")]
 
 
 class ZedaError(RuntimeError):
@@ -57,13 +58,14 @@ def lib() -> ctypes.CDLL:
         dp = ctypes.POINTER(LayerDesc)
         L.zeda_status_string.restype = ctypes.c_char_p
         L.zeda_status_string.argtypes = [i32]
-        for name in ("zeda_workspace_bytes", "zeda_dispatch_workspace_bytes", "zeda_expert_ffn_workspace_bytes"):
+        for name in ("zeda_workspace_bytes", "zeda_route_workspace_bytes", "zeda_dispatch_workspace_bytes",
+                     "zeda_expert_ffn_workspace_bytes"):
             getattr(L, name).restype = sz
             getattr(L, name).argtypes = [dp]
         L.zeda_workspace_layout.restype = i32
         L.zeda_workspace_layout.argtypes = [dp, ctypes.POINTER(WsLayout)]
         L.zeda_route.restype = i32
-        L.zeda_route.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+        L.zeda_route.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.zeda_dispatch.restype = i32
         L.zeda_dispatch.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.zeda_expert_ffn.restype = i32
@@ -129,9 +131,14 @@ def workspace_layout(desc: LayerDesc) -> WsLayout:
     return out
 
 
-def zeda_route(desc, x, w_router, router_bias, topk_ids, topk_gates, stream=None) -> None:
+def route_workspace_bytes(desc: LayerDesc) -> int:
+    return int(lib().zeda_route_workspace_bytes(ctypes.byref(desc)))
+
+
+def zeda_route(desc, x, w_router, router_bias, topk_ids, topk_gates, ws=None, stream=None) -> None:
+    """ws: uint8 scratch of route_workspace_bytes(desc) or None (see include/zeda.h)."""
     _check(lib().zeda_route(ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(router_bias), _ptr(topk_ids),
-                            _ptr(topk_gates), _stream(stream)), "zeda_route")
+                            _ptr(topk_gates), _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)), "zeda_route")
 
 
 def zeda_dispatch(desc, topk_ids, expert_offsets, sorted_slot, slot_to_row, num_real, ws, stream=None) -> None:

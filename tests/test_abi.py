@@ -53,7 +53,8 @@ def test_workspace_sizes():
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     # fp32 doubles the float buffers; Z = 0 and T = 0 are valid layers
     assert zeda.workspace_bytes(_desc(dtype="f32")) > total
-    assert zeda.workspace_bytes(_desc(Z=0)) == total
+    # Z only changes the router's scratch (one logit table row per token and split)
+    assert total - zeda.route_workspace_bytes(d) == zeda.workspace_bytes(_desc(Z=0)) - zeda.route_workspace_bytes(_desc(Z=0))
     assert zeda.workspace_bytes(_desc(T=0)) > 0
 
 
@@ -71,7 +72,7 @@ def test_descriptor_validation(kw, code):
     assert zeda.lib().zeda_workspace_layout(ctypes.byref(d), ctypes.byref(out)) == code
     # the compute entry points refuse the same descriptor before touching any pointer
     p = ctypes.c_void_p(4096)
-    assert zeda.lib().zeda_route(ctypes.byref(d), p, p, None, p, p, None) == code
+    assert zeda.lib().zeda_route(ctypes.byref(d), p, p, None, p, p, None, 0, None) == code
     assert zeda.lib().zeda_moe_forward(ctypes.byref(d), p, p, None, p, p, p, p, None, p, 1 << 40, None) == code
 
 
@@ -114,9 +115,14 @@ def test_pointer_and_workspace_errors_return_before_any_launch():
     odd = ctypes.c_void_p((1 << 20) + 8)
     need = zeda.workspace_bytes(d)
     dp = ctypes.byref(d)
-    assert lib.zeda_route(dp, None, ok, None, ok, ok, None) == zeda.ZEDA_EINVAL
-    assert lib.zeda_route(dp, odd, ok, None, ok, ok, None) == zeda.ZEDA_EINVAL
-    assert lib.zeda_route(dp, ok, ok, odd, ok, ok, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_route(dp, None, ok, None, ok, ok, None, 0, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_route(dp, odd, ok, None, ok, ok, None, 0, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_route(dp, ok, ok, odd, ok, ok, None, 0, None) == zeda.ZEDA_EINVAL
+    assert lib.zeda_route(dp, ok, ok, None, ok, ok, odd, 1 << 40, None) == zeda.ZEDA_EINVAL
+    small = _desc(T=64)  # few token blocks: the router wants scratch for its split-k launch
+    assert zeda.route_workspace_bytes(small) > 0
+    assert lib.zeda_route(ctypes.byref(small), ok, ok, None, ok, ok, ok, zeda.route_workspace_bytes(small) - 1, None) == zeda.ZEDA_EWORKSPACE
+    assert zeda.route_workspace_bytes(_desc(T=16384)) == 0 and zeda.route_workspace_bytes(_desc(dtype="f32", H=256, I=128)) == 0
     assert lib.zeda_dispatch(dp, ok, ok, ok, ok, ok, None, need, None) == zeda.ZEDA_EINVAL
     assert lib.zeda_dispatch(dp, ok, ok, ok, ok, ok, ok, zeda.dispatch_workspace_bytes(d) - 1, None) == zeda.ZEDA_EWORKSPACE
     assert lib.zeda_expert_ffn(dp, ok, ok, ok, ok, ok, ok, ok, None, ok, need, None) == zeda.ZEDA_EINVAL

@@ -44,6 +44,28 @@ def test_route_alone(dtype, gate_norm):
     assert safe.mean() > 0.8 and np.array_equal(ids.cpu().numpy()[safe], rid0[safe])
 
 
+@pytest.mark.parametrize("T,H", [(203, 1024), (64, 2048), (5, 512), (1000, 384)])
+def test_route_with_scratch_splits_the_hidden_dimension(T, H):
+    # few token blocks: with scratch several workgroups share a block (each a slice of H) and a second kernel
+    # selects; the result must be the oracle's either way
+    w = synth.Workload("route_ws", T=T, H=H, I=64, N=70, Z=27, K=6, dtype="bf16", seed=52, recipe="zero_bias",
+                       wr_std=0.05, zero_bias=0.35)
+    print(w, flush=True)
+    L = harness.gapped_layer(w, "cuda")
+    d = desc_of(w)
+    nbytes = zeda.route_workspace_bytes(d)
+    assert (nbytes > 0) == (H % 128 == 0 and T < 256 * 32)
+    a = harness.to_arrays(L)
+    rid, rg = orc.route(a["x"], a["w_router"], a["router_bias"], w.N, w.Z, w.K)
+    for ws in (torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda"), None):
+        ids = torch.full((w.T, w.K), -1, dtype=torch.int32, device="cuda")
+        gates = torch.full((w.T, w.K), float("nan"), dtype=torch.float32, device="cuda")
+        zeda.zeda_route(d, L["x"], L["w_router"], L["router_bias"], ids, gates, ws=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(ids.cpu().numpy(), rid)
+        np.testing.assert_allclose(gates.cpu().numpy().astype(np.float64), rg, rtol=2e-5, atol=1e-7)
+
+
 def _dispatch(ids_np, N, Z, K):
     T = ids_np.shape[0]
     d = zeda.make_desc(T, 128, 64, N, Z, K, "bf16")
