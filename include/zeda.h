@@ -160,7 +160,7 @@ int zeda_moe_forward_events(const zeda_layer_desc *desc, const void *x, const vo
 /* Rewrites the expert weights of a layer from row-major into ZEDA_WEIGHTS_TILED (one-time, outside the hot
  * path; the layer of Section 2.1 does not depend on how its weights are stored).  For a matrix W[F][Kd]
  * (W_gate[e], W_up[e]: F = I, Kd = H; W_down[e]: F = H, Kd = I) the output holds (F/32) x (Kd/32) blocks of
- * 2 KiB, block (rb, kb) at index rb * (Kd/32) + kb; a block stores rows 32rb.., columns 32kb.. as 32 rows of
+ * 2 KiB, block (rb, kb) at index kb * (F/32) + rb; a block stores rows 32rb.., columns 32kb.. as 32 rows of
  * 64 bytes whose four 16-byte pieces are permuted: piece p of row r sits at position p ^ ((r >> 2) & 3).
  * Experts follow each other as in the input.  Any of the three pairs may be NULL/NULL (skipped); in and out
  * must not overlap.  desc->dtype must be bf16 (ZEDA_EUNSUPPORTED otherwise); desc->T and weight_layout are

@@ -226,7 +226,7 @@ struct Stream {
                     const int lb = jw >> 1, blk = lb % FB, wfr = lb / FB;
                     const bf16_t *wbase = (GATEUP && (blk & 1)) ? w1 : w0;
                     const int rb = GATEUP ? ft * (BF / 64) + wfr * (FB / 2) + (blk >> 1) : ft * (BF / 32) + lb;
-                    src[i] = wbase + ((size_t)expert * (Fdim / 32) + rb) * (Kdim / 32) * 1024 + (jw & 1) * 512 + ln * 8;
+                    src[i] = wbase + ((size_t)expert * (Kdim / 32) * (Fdim / 32) + rb) * 1024 + (jw & 1) * 512 + ln * 8;
                 } else {
                     const int row = jw * RPI + rsub;
                     const bf16_t *wbase;
@@ -262,7 +262,7 @@ struct Stream {
     __device__ __forceinline__ void issue_one(int i, int ni)
     {
         if (i < ni) {
-            const int step = (TILED && wrole) ? 1024 : KC;  // elements from one chunk to the next
+            const int step = (TILED && wrole) ? (Fdim / 32) * 1024 : KC;  // elements from one chunk to the next
             unsigned char *dst = wrole ? wring + islot * WST + (wave + NWW * i) * 1024
                                        : tring + islot * TST + (wave - NWW + NWT * i) * 1024;
             __builtin_amdgcn_global_load_lds(ZEDA_GLOBAL_PTR(src[i] + (size_t)ikc * step), ZEDA_LDS_PTR(dst), 16, 0, 0);
@@ -327,10 +327,8 @@ struct Stream {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-        // first chunk of the item: wait, meet, refill the slot everybody has just left
-        wait_oldest();
-        __builtin_amdgcn_s_barrier();
-        issue_burst();
+        // On entry the item's first chunk has landed and everybody has met after waiting for it (the item before,
+        // or the start of the stream, saw to that).
         bf16x8 fa[2][FB], tb[2][GA];
         load_frags<GA>(wring + cslot_w * WST, tring + cslot_t * TST, 0, fa[0], tb[0]);
 
@@ -347,12 +345,14 @@ struct Stream {
                 } else {
                     // every fragment of this chunk is in registers: nobody needs its slot any more
                     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-                    if (more) {
-                        wait_oldest();
-                        __builtin_amdgcn_s_barrier();
-                        load_frags<GA>(wring + nslot_w * WST, tring + nslot_t * TST, 0, fa[p ^ 1], tb[p ^ 1]);
-                        ni = inl;
-                    }
+                    // Wait for the next chunk, meet, refill the slot everybody has just left.  After the item's last
+                    // chunk the next chunk is the first one of the next item (nothing, at the end of the stream): it is
+                    // awaited HERE, before the epilogue, because the epilogue's stores count in vmcnt too - a wait
+                    // right after them would have to sit out their whole round trip.
+                    wait_oldest();
+                    __builtin_amdgcn_s_barrier();
+                    if (more) load_frags<GA>(wring + nslot_w * WST, tring + nslot_t * TST, 0, fa[p ^ 1], tb[p ^ 1]);
+                    ni = inl;
                 }
                 // keep the reads of the next step ahead of this step's MFMAs
                 __builtin_amdgcn_sched_barrier(0);
@@ -371,7 +371,7 @@ struct Stream {
                         }
                     }
                 __builtin_amdgcn_sched_barrier(0);
-                if (s == KS - 1 && more) issued(ni);
+                if (s == KS - 1) issued(ni);
             }
             cslot_w = nslot_w;
             cslot_t = nslot_t;
@@ -503,7 +503,10 @@ __global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__re
         for (int h = 0; h < Stream<C, GATEUP, TILED>::NH; ++h) st.hist[h] = 0;
         st.setup_issue_item();
         for (int c = 0, n = (st.wrole ? C::NSW : C::NST) - 1; c < n; ++c) st.issue_burst();
-        // all slots of this wave's ring but one are in flight; the first wait is for the oldest
+        // all slots of this wave's ring but one are in flight: wait for the first chunk, meet, fill the last slot
+        st.wait_oldest();
+        __builtin_amdgcn_s_barrier();
+        st.issue_burst();
 
         for (int q = 0; q < nq; ++q) {
             const int4 loc = st.read_loc(q);
@@ -513,7 +516,8 @@ __global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__re
 }
 
 // Tiled weight layout.  A matrix W[F][Kd] (F, Kd multiples of 32) is stored as (F/32) x (Kd/32) units of 2 KiB,
-// unit (rb, kb) at index rb * (Kd/32) + kb, so that the k blocks of one 32-row block follow each other.  A
+// unit (rb, kb) at index kb * (F/32) + rb, so that the row blocks of one k block follow each other: the
+// consecutive row blocks of a feature tile are then one contiguous run of 8-16 KiB per k chunk.  A
 // unit holds rows 32rb..32rb+31, columns 32kb..32kb+31 as 32 rows of 64 bytes, the four 16-byte pieces of
 // row r permuted as in the LDS ring (piece p at position p ^ ((r >> 2) & 3)): it is the LDS image of that
 // block, so the GEMM copies it with contiguous 1 KiB loads - which is what lets HBM stream at full rate
@@ -528,7 +532,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t *__restr
     const size_t unit = idx >> 7;
     const int kbs = Kd / 32, units_per_mat = (F / 32) * kbs;
     const size_t mat = unit / units_per_mat;
-    const int u = (int)(unit - mat * units_per_mat), rb = u / kbs, kb = u - rb * kbs;
+    const int u = (int)(unit - mat * units_per_mat), rbs = F / 32, kb = u / rbs, rb = u - kb * rbs;
     const int p = pos ^ ((r >> 2) & 3);
     const bf16x8 v = *reinterpret_cast<const bf16x8 *>(w + (mat * F + rb * 32 + r) * Kd + kb * 32 + p * 8);
     *reinterpret_cast<bf16x8 *>(out + idx * 8) = v;

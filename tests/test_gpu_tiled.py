@@ -17,10 +17,10 @@ def _say(*a):
 
 
 def tiled_reference(w: np.ndarray) -> np.ndarray:
-    """include/zeda.h, zeda_pack_expert_weights: [mats, F, Kd] -> blocks (rb, kb) of 32 rows x 32 columns, kb
+    """include/zeda.h, zeda_pack_expert_weights: [mats, F, Kd] -> blocks (rb, kb) of 32 rows x 32 columns, rb
     fastest; inside a block 32 rows of four 8-element pieces, piece p of row r at position p ^ ((r >> 2) & 3)."""
     mats, F, Kd = w.shape
-    b = w.reshape(mats, F // 32, 32, Kd // 32, 4, 8).transpose(0, 1, 3, 2, 4, 5)  # mats, rb, kb, r, p, 8
+    b = w.reshape(mats, F // 32, 32, Kd // 32, 4, 8).transpose(0, 3, 1, 2, 4, 5)  # mats, kb, rb, r, p, 8
     out = np.empty_like(b)
     for r in range(32):
         for p in range(4):
