@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # profiles/ffn_kernels_c2_qwen_prefill_hbm_traffic.txt (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB, both scales read
 # off a plain copy kernel in the same runs).  Counters cannot be read from inside this process, so the figure is
 # only reported for the workload and weight layout it was measured on.
-MEASURED_GATEUP_TRAFFIC_BYTES = {("c2_qwen_prefill", "tiled"): 906.0e6}
+MEASURED_GATEUP_TRAFFIC_BYTES = {("c2_qwen_prefill", "tiled"): 911.9e6}
 CPU_BASELINE_SECONDS = 12.0      # the oracle keeps making passes over its token sample until this much time has gone by
 
 
@@ -119,6 +119,9 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload (sequence-length sweeps)")
     ap.add_argument("--weights", default="tiled", choices=["tiled", "row_major"],
                     help="storage of the expert weights: packed once into the library's tiled layout (default), or row-major")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one plain elementwise kernel that reads and writes 2^28 bytes (a yardstick for "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters; outside the timed region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-z0", action="store_true")
     a = ap.parse_args()
@@ -130,6 +133,13 @@ def main() -> int:
         print("bench.py needs a GPU (the HIP library has no CPU fallback)", file=sys.stderr)
         return 2
     zeda.lib()
+    if a.calibration_copy:
+        src = torch.arange(1 << 26, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.bitwise_xor(src, 0x55, out=dst)  # one kernel: 268,435,456 bytes in, 268,435,456 bytes out
+        torch.cuda.synchronize()
+        del src, dst
     if a.workload == "c5_stack":
         return stack_bench(a)
 
