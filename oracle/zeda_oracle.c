@@ -125,6 +125,50 @@ int oracle_route(const float *x, const float *wr, const float *bias, int T, int 
     return 0;
 }
 
+/* Batch routing statistics of Section 2.2 (Eq. 4-6) for one layer, all tokens forming the batch B:
+ *   f[i] = fraction of tokens whose top-K set holds expert i            (sums to K over i)
+ *   P[i] = mean over tokens of the routing probability of expert i     (softmax over all N+Z logits; sums to 1)
+ *   group sums f_E, P_E over the N normal experts and f_Z, P_Z over the Z zero experts,
+ *   L_A  = alpha (N+Z)/K  sum_i f[i] P[i]                               (Eq. 4)
+ *   L_GA = alpha (N+Z w)/K ( f_E P_E / N + f_Z P_Z / (Z w) )            (Eq. 5-6; the second term is dropped at Z = 0)
+ *   r_ZE = f_Z / K.
+ * summary[7] = {f_E, P_E, f_Z, P_Z, r_ZE, L_A, L_GA}.  Plain serial loops (the sums are over tokens). */
+int oracle_routing_stats(const float *x, const float *wr, const float *bias, int T, int H, int N, int Z, int K,
+                         double alpha, double w, double *f, double *P, double *summary)
+{
+    const int NE = N + Z;
+    if (T < 1 || H < 1 || N < 1 || Z < 0 || K < 1 || K > NE || !(w > 0.0)) return -1;
+    double *logit = (double *)malloc(sizeof(double) * NE);
+    char *taken = (char *)malloc((size_t)NE);
+    int32_t *ids = (int32_t *)malloc(sizeof(int32_t) * K);
+    double *gates = (double *)malloc(sizeof(double) * K);
+    for (int e = 0; e < NE; ++e) f[e] = P[e] = 0.0;
+    for (int t = 0; t < T; ++t) {
+        token_logits(x + (size_t)t * H, wr, bias, H, NE, logit);
+        token_select(logit, N, NE, K, GATE_SOFTMAX, ids, gates, taken);
+        for (int j = 0; j < K; ++j) f[ids[j]] += 1.0;
+        double mx = logit[0];
+        for (int e = 1; e < NE; ++e) if (logit[e] > mx) mx = logit[e];
+        double all = 0.0;
+        for (int e = 0; e < NE; ++e) all += exp(logit[e] - mx);
+        for (int e = 0; e < NE; ++e) P[e] += exp(logit[e] - mx) / all;
+    }
+    double fE = 0.0, PE = 0.0, fZ = 0.0, PZ = 0.0, dot = 0.0;
+    for (int e = 0; e < NE; ++e) {
+        f[e] /= (double)T;
+        P[e] /= (double)T;
+        dot += f[e] * P[e];
+        if (e < N) { fE += f[e]; PE += P[e]; } else { fZ += f[e]; PZ += P[e]; }
+    }
+    summary[0] = fE; summary[1] = PE; summary[2] = fZ; summary[3] = PZ;
+    summary[4] = fZ / (double)K;
+    summary[5] = alpha * (double)NE / (double)K * dot;
+    summary[6] = alpha * ((double)N + (double)Z * w) / (double)K *
+                 (fE * PE / (double)N + (Z > 0 ? fZ * PZ / ((double)Z * w) : 0.0));
+    free(logit); free(taken); free(ids); free(gates);
+    return 0;
+}
+
 /* One normal expert on one token (Appendix D: gate, up and down projections; SwiGLU reading):
  * y = W_down ( silu(W_gate h) * (W_up h) ).  act is scratch of I doubles. */
 static void expert_apply(const float *xt, const float *wg, const float *wu, const float *wd, int H, int I,

@@ -39,6 +39,7 @@ def _load():
         _lib.oracle_flop_ratio.restype = ctypes.c_double
         _lib.oracle_flop_ratio.argtypes = [ctypes.c_int] + [ctypes.c_double] * 9
         _lib.oracle_num_threads.restype = ctypes.c_int
+        _lib.oracle_routing_stats.restype = ctypes.c_int
     return _lib
 
 
@@ -151,6 +152,24 @@ def rmsnorm(x, gamma=None, eps: float = 1e-6) -> np.ndarray:
     out = np.empty_like(x)
     lib.oracle_rmsnorm(_p(x), _p(g), T, H, ctypes.c_double(eps), _p(out))
     return out
+
+
+def routing_stats(x, w_router, router_bias, N: int, Z: int, K: int, alpha: float = 1.0, w: float = 1.0):
+    """Section 2.2, Eq. 4-6 on the batch of all tokens: dict(f[N+Z], P[N+Z], f_E, P_E, f_Z, P_Z, r_ze, L_A, L_GA)."""
+    lib = _load()
+    x = _f32(x)
+    T, H = x.shape
+    wr = _f32(w_router, (N + Z, H))
+    b = _f32(router_bias, (N + Z,)) if router_bias is not None else None
+    f = np.empty(N + Z, dtype=np.float64)
+    P = np.empty(N + Z, dtype=np.float64)
+    summ = np.empty(7, dtype=np.float64)
+    rc = lib.oracle_routing_stats(_p(x), _p(wr), _p(b), T, H, N, Z, K, ctypes.c_double(alpha), ctypes.c_double(w), _p(f),
+                                  _p(P), _p(summ))
+    if rc != 0:
+        raise ValueError("oracle_routing_stats: bad arguments")
+    keys = ("f_E", "P_E", "f_Z", "P_Z", "r_ze", "L_A", "L_GA")
+    return {"f": f, "P": P, **{k: float(v) for k, v in zip(keys, summ)}}
 
 
 def moe_flops(n, H, He, N, NZ, K, r_ze) -> float:

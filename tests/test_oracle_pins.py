@@ -310,3 +310,66 @@ def test_argument_errors():
         orc.route(L["x"], L["wr"], None, 2, 1, 4)  # K > N + Z
     with pytest.raises(ValueError):
         orc.route(L["x"], L["wr"], None, 2, 1, 1, gate_norm=7)
+
+
+# ----------------------------------------------------------------------------------------------
+# Routing statistics of Section 2.2 (Eq. 4-6)
+# ----------------------------------------------------------------------------------------------
+def _stats_reference(L, N, Z, K, alpha, w):
+    """Eq. 4-6 written out with library softmax, a stable sort and one-hot sums (no per-token loop)."""
+    logits = L["x"].astype(np.float64) @ L["wr"].astype(np.float64).T
+    p = softmax(logits, axis=1)
+    order = np.argsort(-logits.astype(np.float32), axis=1, kind="stable")[:, :K]
+    onehot = np.zeros_like(p)
+    np.put_along_axis(onehot, order, 1.0, axis=1)
+    f, P = onehot.mean(axis=0), p.mean(axis=0)
+    fE, PE, fZ, PZ = f[:N].sum(), P[:N].sum(), f[N:].sum(), P[N:].sum()
+    LA = alpha * (N + Z) / K * float(f @ P)
+    LGA = alpha * (N + Z * w) / K * (fE * PE / N + (fZ * PZ / (Z * w) if Z else 0.0))
+    return f, P, fE, PE, fZ, PZ, LA, LGA
+
+
+@pytest.mark.parametrize("N,Z,K,w", [(6, 3, 2, 2.0), (8, 4, 3, 0.5), (5, 0, 2, 1.0)])
+def test_routing_stats_against_the_written_out_definition(N, Z, K, w):
+    L = _rand_layer(61, T=97, H=24, I=8, N=N, Z=Z, scale_r=0.7)
+    s = orc.routing_stats(L["x"], L["wr"], None, N, Z, K, alpha=0.01, w=w)
+    f, P, fE, PE, fZ, PZ, LA, LGA = _stats_reference(L, N, Z, K, 0.01, w)
+    np.testing.assert_allclose(s["f"], f, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(s["P"], P, rtol=1e-12, atol=1e-15)
+    for got, want in ((s["f_E"], fE), (s["P_E"], PE), (s["f_Z"], fZ), (s["P_Z"], PZ), (s["L_A"], LA), (s["L_GA"], LGA)):
+        assert got == pytest.approx(want, rel=1e-12, abs=1e-15)
+    # invariants: every token fills K slots, probabilities sum to one, r_ZE is the zero group's share of the slots
+    assert s["f"].sum() == pytest.approx(K, abs=1e-12) and s["P"].sum() == pytest.approx(1.0, abs=1e-12)
+    assert s["r_ze"] == pytest.approx(s["f_Z"] / K, abs=1e-15)
+
+
+def test_routing_stats_closed_forms():
+    # A router whose rows are all equal gives every expert probability 1/(N+Z), whatever is selected, so Eq. 4
+    # collapses to alpha * (N+Z)/K * (sum f_i)/(N+Z) = alpha; ties go to the lowest indices, so the K slots are
+    # all on normal experts: f_E = K, f_Z = 0, P_E = N/(N+Z), and Eq. 5 gives alpha * (N + Z w)/(N + Z).
+    N, Z, K, w, alpha = 7, 5, 3, 2.5, 0.3
+    L = _rand_layer(62, T=40, H=16, I=8, N=N, Z=Z)
+    L["wr"][:] = L["wr"][0]
+    s = orc.routing_stats(L["x"], L["wr"], None, N, Z, K, alpha=alpha, w=w)
+    np.testing.assert_allclose(s["P"], 1.0 / (N + Z), rtol=1e-12)
+    np.testing.assert_allclose(s["f"], [1.0] * K + [0.0] * (N + Z - K), atol=0)
+    assert s["L_A"] == pytest.approx(alpha, rel=1e-12)
+    assert s["L_GA"] == pytest.approx(alpha * (N + Z * w) / (N + Z), rel=1e-12)
+    # At the balance point of Section 2.2 (slots and probability split N : Z w between the groups) Eq. 5 equals
+    # alpha as well.  Built by hand: a bias that sends exactly the share r* = Z w/(N + Z w) of the tokens to
+    # zero experts is awkward to construct, so the identity is checked on the formula's own inputs instead:
+    r = Z * w / (N + Z * w)
+    fE, fZ, PE, PZ = K * (1 - r), K * r, 1 - r, r
+    assert alpha * (N + Z * w) / K * (fE * PE / N + fZ * PZ / (Z * w)) == pytest.approx(alpha, rel=1e-12)
+
+
+def test_routing_stats_bias_moves_slots_to_the_zero_group():
+    # a large bias on the zero experts routes every slot there: f_Z = K, r_ZE = 1, and P_Z -> 1
+    N, Z, K = 6, 4, 3
+    L = _rand_layer(63, T=50, H=16, I=8, N=N, Z=Z, scale_r=0.3)
+    bias = np.zeros(N + Z, dtype=np.float32)
+    bias[N:] = 40.0
+    s = orc.routing_stats(L["x"], L["wr"], bias, N, Z, K)
+    assert s["f_Z"] == pytest.approx(K) and s["r_ze"] == pytest.approx(1.0) and s["P_Z"] > 1 - 1e-9
+    with pytest.raises(ValueError):
+        orc.routing_stats(L["x"], L["wr"], None, N, Z, K, w=0.0)
