@@ -168,6 +168,20 @@ int zeda_moe_forward_events(const zeda_layer_desc *desc, const void *x, const vo
 int zeda_pack_expert_weights(const zeda_layer_desc *desc, const void *w_gate, const void *w_up, const void *w_down,
                              void *w_gate_tiled, void *w_up_tiled, void *w_down_tiled, void *stream);
 
+/* Batch routing statistics of Section 2.2 for one layer, the T tokens of the call being the batch B (forward
+ * values only; nothing is differentiated):
+ *   f[i] = fraction of tokens whose top-K set holds expert i, P[i] = mean over tokens of the routing probability
+ *   of expert i (softmax over all N+Z logits - the reading taken for "mean routing probability"), i in [0, N+Z);
+ *   summary[0..6] = f_E, P_E, f_Z, P_Z (sums over the normal / the zero experts), r_ZE = f_Z / K,
+ *   L_A = alpha (N+Z)/K sum_i f[i] P[i] (Eq. 4),  L_GA = alpha (N + Z w)/K (f_E P_E / N + f_Z P_Z / (Z w)) (Eq. 5-6;
+ *   the zero-group term is dropped at Z = 0).
+ * f, P, summary: device, fp32.  w > 0 is the group weight of Eq. 5.  T >= 1.  desc->gate_norm is not used.
+ * ws: scratch of zeda_routing_stats_workspace_bytes(desc).  All sums run in a fixed order. */
+size_t zeda_routing_stats_workspace_bytes(const zeda_layer_desc *desc);
+int zeda_routing_stats(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,
+                       float alpha, float w, float *f /*[N+Z]*/, float *P /*[N+Z]*/, float *summary /*[7]*/, void *ws,
+                       size_t ws_bytes, void *stream);
+
 /* Byte offsets inside the forward workspace (host-only).  Returns ZEDA_OK or an error. */
 typedef struct {
     size_t topk_ids, topk_gates, expert_offsets, sorted_slot, slot_to_row, num_real, dispatch_ws, act, y_slot, route_ws,

@@ -233,6 +233,26 @@ int zeda_moe_forward_events(const zeda_layer_desc *desc, const void *x, const vo
                         events);
 }
 
+size_t zeda_routing_stats_workspace_bytes(const zeda_layer_desc *desc)
+{
+    if (check_desc(desc) != ZEDA_OK) return 0;
+    return routing_stats_ws_bytes(desc);
+}
+
+int zeda_routing_stats(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,
+                       float alpha, float w, float *f, float *P, float *summary, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != ZEDA_OK) return rc;
+    if (!x || !w_router || !f || !P || !summary || !ws || desc->T < 1 || !(w > 0.f)) return ZEDA_EINVAL;
+    if (!aligned16(x) || !aligned16(w_router) || !aligned16(ws) || (router_bias && !aligned16(router_bias)) ||
+        (reinterpret_cast<uintptr_t>(f) & 3u) || (reinterpret_cast<uintptr_t>(P) & 3u) ||
+        (reinterpret_cast<uintptr_t>(summary) & 3u))
+        return ZEDA_EINVAL;
+    if (ws_bytes < routing_stats_ws_bytes(desc)) return ZEDA_EWORKSPACE;
+    return launch_routing_stats(desc, x, w_router, router_bias, alpha, w, f, P, summary, ws, (hipStream_t)stream);
+}
+
 int zeda_pack_expert_weights(const zeda_layer_desc *desc, const void *w_gate, const void *w_up, const void *w_down,
                              void *w_gate_tiled, void *w_up_tiled, void *w_down_tiled, void *stream)
 {

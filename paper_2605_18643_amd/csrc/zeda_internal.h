@@ -29,6 +29,10 @@ inline size_t elt_size(const zeda_layer_desc *d) { return d->dtype == ZEDA_BF16 
 int launch_route(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
                  float *gates, float *partial, hipStream_t s);
 size_t route_ws_bytes(const zeda_layer_desc *d);
+// Section 2.2 statistics over the batch of all T tokens (f, P: [N+Z]; summary: 7 floats); ws of routing_stats_ws_bytes
+int launch_routing_stats(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, float alpha, float w,
+                         float *f, float *P, float *summary, void *ws, hipStream_t s);
+size_t routing_stats_ws_bytes(const zeda_layer_desc *d);
 // num_real_copy (may be NULL) receives num_real as well
 int launch_dispatch(const zeda_layer_desc *d, const int32_t *ids, int32_t *offsets, int32_t *sorted_slot,
                     int32_t *slot_to_row, int32_t *num_real, int32_t *num_real_copy, hipStream_t s);

@@ -283,7 +283,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_f32_kernel(const float *_
                                                                   const float *__restrict__ wr,
                                                                   const float *__restrict__ bias, int T, int H, int N,
                                                                   int NE, int K, int gate_norm,
-                                                                  int32_t *__restrict__ ids, float *__restrict__ gates)
+                                                                  int32_t *__restrict__ ids, float *__restrict__ gates,
+                                                                  float *__restrict__ logits_out, int LDg)
 {
     __shared__ float xs[kRouteF32Tokens * kRouteF32Chunk];
     __shared__ float lg[kRouteF32Tokens * (kMaxExperts + 1)];
@@ -318,6 +319,11 @@ __global__ __launch_bounds__(kRouteThreads) void route_f32_kernel(const float *_
         }
     }
     __syncthreads();
+    if (logits_out) {  // statistics run: hand the logits (without the bias) to route_stats_kernel
+        for (int i = tid; i < kRouteF32Tokens * NE; i += kRouteThreads)
+            logits_out[(size_t)(t0 + i / NE) * LDg + (i % NE)] = lg[(i / NE) * LD + (i % NE)];
+        return;
+    }
     select_block<kMaxExperts / 16, 1, 4>(lg, LD, 0, 1, bias, kRouteF32Tokens, t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
@@ -342,7 +348,7 @@ size_t route_ws_bytes(const zeda_layer_desc *d)
 
 template <int NB>
 static void launch_route_bf16(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
-                              float *gates, float *partial, hipStream_t s)
+                              float *gates, float *partial, hipStream_t s, bool logits_only = false)
 {
     const int blocks = ceil_div(d->T, kRouteTokens), Tpad = blocks * kRouteTokens;
     const int c = partial ? route_ksplit(d) : 1;
@@ -354,7 +360,8 @@ static void launch_route_bf16(const zeda_layer_desc *d, const void *x, const voi
     }
     route_bf16_kernel<NB><<<dim3(blocks, c), kRouteThreads, lds_bytes, s>>>(
         (const bf16_t *)x, (const bf16_t *)wr, bias, d->T, d->H, d->N, d->N + d->Z, d->K, d->gate_norm, ids, gates,
-        c > 1 ? partial : nullptr, Tpad);
+        (c > 1 || logits_only) ? partial : nullptr, Tpad);
+    if (logits_only) return;
     const dim3 sgrid(ceil_div(d->T, kSelectTokens));
     const int NE = d->N + d->Z;
     if (c == 2)
@@ -363,6 +370,187 @@ static void launch_route_bf16(const zeda_layer_desc *d, const void *x, const voi
         route_select_kernel<NB, 4><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates);
     else if (c == 8)
         route_select_kernel<NB, 8><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Batch routing statistics (Section 2.2, Eq. 4-6): f_i, P_i, the group sums and the forward values of the
+// two auxiliary losses, over all T tokens as the batch.  Three steps: logits (the router kernels above, writing
+// their tables to scratch), per-block sums (route_stats_kernel), one final workgroup (route_stats_final_kernel).
+// Every floating-point sum runs in a fixed order.
+// ---------------------------------------------------------------------------------------------
+constexpr int kStatsTokens = 64;  // tokens per workgroup of route_stats_kernel: four batches of four per wave
+
+template <int NC>
+__global__ __launch_bounds__(kRouteThreads) void route_stats_kernel(const float *__restrict__ logits, int nsplit, int Tpad,
+                                                                    int LDg, const float *__restrict__ bias, int T, int NE,
+                                                                    int K, float *__restrict__ p_part,
+                                                                    int32_t *__restrict__ f_part)
+{
+    __shared__ float s_p[16][kMaxExperts];
+    __shared__ int s_f[16][kMaxExperts];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, row = lane >> 4;
+    const int t0 = blockIdx.x * kStatsTokens;
+    float psum[NC];
+    int fcnt[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) { psum[c] = 0.f; fcnt[c] = 0; }
+    for (int batch = 0; batch < kStatsTokens / 16; ++batch) {
+        const int t = t0 + batch * 16 + wave * 4 + row;
+        const bool ok = t < T;
+        float cand[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) cand[c] = -INFINITY;
+        if (ok) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                if (l16 + 16 * c < NE) cand[c] = logits[(size_t)t * LDg + l16 + 16 * c];
+            for (int q = 1; q < nsplit; ++q) {
+#pragma unroll
+                for (int c = 0; c < NC; ++c)
+                    if (l16 + 16 * c < NE) cand[c] += logits[((size_t)q * Tpad + t) * LDg + l16 + 16 * c];
+            }
+            if (bias) {
+#pragma unroll
+                for (int c = 0; c < NC; ++c)
+                    if (l16 + 16 * c < NE) cand[c] += bias[l16 + 16 * c];
+            }
+        }
+        // probabilities: softmax over all N+Z logits of the token (the row)
+        float m = cand[0];
+#pragma unroll
+        for (int c = 1; c < NC; ++c) m = fmaxf(m, cand[c]);
+        m = row_max(m);
+        float ex[NC], sacc = 0.f;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            ex[c] = (ok && l16 + 16 * c < NE) ? expf(cand[c] - m) : 0.f;
+            sacc += ex[c];
+        }
+        const float all = row_sum(sacc);
+        if (ok) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c) psum[c] += ex[c] / all;
+        }
+        // the top-K set, as in select_rows: K rounds of (row maximum, lowest index among equals)
+        for (int j = 0; j < K; ++j) {
+            float mm = cand[0];
+#pragma unroll
+            for (int c = 1; c < NC; ++c) mm = fmaxf(mm, cand[c]);
+            mm = row_max(mm);
+            int mine = INT_MAX;
+#pragma unroll
+            for (int c = NC - 1; c >= 0; --c)
+                if (cand[c] == mm) mine = l16 + 16 * c;
+            const int win = row_min(mine);
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                if (win == l16 + 16 * c) {
+                    cand[c] = -INFINITY;
+                    if (ok) ++fcnt[c];
+                }
+        }
+    }
+    // 16 (wave, row) partial tables -> one per workgroup, added in table order
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        s_p[wave * 4 + row][l16 + 16 * c] = psum[c];
+        s_f[wave * 4 + row][l16 + 16 * c] = fcnt[c];
+    }
+    __syncthreads();
+    if (tid < NE) {
+        float ps = 0.f;
+        int fs = 0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { ps += s_p[r][tid]; fs += s_f[r][tid]; }
+        p_part[(size_t)blockIdx.x * NE + tid] = ps;
+        f_part[(size_t)blockIdx.x * NE + tid] = fs;
+    }
+}
+
+__global__ __launch_bounds__(kRouteThreads) void route_stats_final_kernel(const float *__restrict__ p_part,
+                                                                          const int32_t *__restrict__ f_part, int nblocks,
+                                                                          int T, int N, int NE, int K, float alpha, float w,
+                                                                          float *__restrict__ f, float *__restrict__ P,
+                                                                          float *__restrict__ summary)
+{
+    __shared__ float s_f[kMaxExperts], s_P[kMaxExperts];
+    const int e = threadIdx.x;
+    if (e < NE) {
+        float ps = 0.f;
+        long long fs = 0;
+        for (int b = 0; b < nblocks; ++b) { ps += p_part[(size_t)b * NE + e]; fs += f_part[(size_t)b * NE + e]; }
+        s_P[e] = ps / (float)T;
+        s_f[e] = (float)((double)fs / (double)T);
+        f[e] = s_f[e];
+        P[e] = s_P[e];
+    }
+    __syncthreads();
+    if (e == 0) {
+        float fE = 0.f, PE = 0.f, fZ = 0.f, PZ = 0.f, dot = 0.f;
+        for (int i = 0; i < NE; ++i) {
+            dot += s_f[i] * s_P[i];
+            if (i < N) { fE += s_f[i]; PE += s_P[i]; } else { fZ += s_f[i]; PZ += s_P[i]; }
+        }
+        const int Z = NE - N;
+        summary[0] = fE; summary[1] = PE; summary[2] = fZ; summary[3] = PZ;
+        summary[4] = fZ / (float)K;
+        summary[5] = alpha * (float)NE / (float)K * dot;                                   // Eq. 4
+        summary[6] = alpha * ((float)N + (float)Z * w) / (float)K *
+                     (fE * PE / (float)N + (Z > 0 ? fZ * PZ / ((float)Z * w) : 0.f));       // Eq. 5-6
+    }
+}
+
+// scratch: the logit tables, then the per-block sums
+static size_t stats_logits_bytes(const zeda_layer_desc *d)
+{
+    const size_t Tpad = (size_t)ceil_div(d->T, kRouteTokens) * kRouteTokens;
+    return align_up((size_t)route_ksplit(d) * Tpad * ceil_div(d->N + d->Z, 32) * 32 * sizeof(float), 256);
+}
+size_t routing_stats_ws_bytes(const zeda_layer_desc *d)
+{
+    const size_t nblk = (size_t)ceil_div(d->T, kStatsTokens), NE = (size_t)(d->N + d->Z);
+    return stats_logits_bytes(d) + align_up(nblk * NE * 4, 256) * 2;
+}
+
+int launch_routing_stats(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, float alpha, float w,
+                         float *f, float *P, float *summary, void *ws, hipStream_t s)
+{
+    const int NE = d->N + d->Z, NB = ceil_div(NE, 32), LDg = NB * 32;
+    const int Tpad = ceil_div(d->T, kRouteTokens) * kRouteTokens, nblk = ceil_div(d->T, kStatsTokens);
+    float *logits = (float *)ws;
+    float *p_part = (float *)((char *)ws + stats_logits_bytes(d));
+    int32_t *f_part = (int32_t *)((char *)p_part + align_up((size_t)nblk * NE * 4, 256));
+    int nsplit = 1;
+    if (d->dtype == ZEDA_BF16) {
+        nsplit = route_ksplit(d);
+        switch (NB) {
+            case 1: launch_route_bf16<1>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 2: launch_route_bf16<2>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 3: launch_route_bf16<3>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 4: launch_route_bf16<4>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 5: launch_route_bf16<5>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 6: launch_route_bf16<6>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 7: launch_route_bf16<7>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            default: launch_route_bf16<8>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+        }
+    } else {
+        route_f32_kernel<<<ceil_div(d->T, kRouteF32Tokens), kRouteThreads, 0, s>>>(
+            (const float *)x, (const float *)wr, bias, d->T, d->H, d->N, NE, d->K, d->gate_norm, nullptr, nullptr, logits, LDg);
+    }
+    if (hipGetLastError() != hipSuccess) return ZEDA_EHIP;
+#define ZEDA_STATS(NC) route_stats_kernel<NC><<<nblk, kRouteThreads, 0, s>>>(logits, nsplit, Tpad, LDg, bias, d->T, NE, d->K, p_part, f_part)
+    switch (ceil_div(NE, 16)) {
+        case 1: ZEDA_STATS(1); break;   case 2: ZEDA_STATS(2); break;   case 3: ZEDA_STATS(3); break;
+        case 4: ZEDA_STATS(4); break;   case 5: ZEDA_STATS(5); break;   case 6: ZEDA_STATS(6); break;
+        case 7: ZEDA_STATS(7); break;   case 8: ZEDA_STATS(8); break;   case 9: ZEDA_STATS(9); break;
+        case 10: ZEDA_STATS(10); break; case 11: ZEDA_STATS(11); break; case 12: ZEDA_STATS(12); break;
+        case 13: ZEDA_STATS(13); break; case 14: ZEDA_STATS(14); break; case 15: ZEDA_STATS(15); break;
+        default: ZEDA_STATS(16); break;
+    }
+#undef ZEDA_STATS
+    if (hipGetLastError() != hipSuccess) return ZEDA_EHIP;
+    route_stats_final_kernel<<<1, kRouteThreads, 0, s>>>(p_part, f_part, nblk, d->T, d->N, NE, d->K, alpha, w, f, P, summary);
+    return last_launch_status();
 }
 
 int launch_route(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
@@ -383,7 +571,7 @@ int launch_route(const zeda_layer_desc *d, const void *x, const void *wr, const 
     } else {
         dim3 grid(ceil_div(d->T, kRouteF32Tokens));
         route_f32_kernel<<<grid, kRouteThreads, 0, s>>>((const float *)x, (const float *)wr, bias, d->T, d->H, d->N, NE,
-                                                        d->K, d->gate_norm, ids, gates);
+                                                        d->K, d->gate_norm, ids, gates, nullptr, 0);
     }
     return last_launch_status();
 }

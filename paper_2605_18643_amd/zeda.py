@@ -24,7 +24,7 @@ STAGES = ("route", "dispatch", "gateup", "down", "combine")
 EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_route_workspace_bytes", "zeda_dispatch_workspace_bytes",
            "zeda_expert_ffn_workspace_bytes", "zeda_workspace_layout", "zeda_route", "zeda_dispatch",
            "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events", "zeda_rmsnorm",
-           "zeda_residual_add", "zeda_pack_expert_weights")
+           "zeda_residual_add", "zeda_pack_expert_weights", "zeda_routing_stats_workspace_bytes", "zeda_routing_stats")
 
 
 class LayerDesc(ctypes.Structure):
@@ -59,7 +59,7 @@ def lib() -> ctypes.CDLL:
         L.zeda_status_string.restype = ctypes.c_char_p
         L.zeda_status_string.argtypes = [i32]
         for name in ("zeda_workspace_bytes", "zeda_route_workspace_bytes", "zeda_dispatch_workspace_bytes",
-                     "zeda_expert_ffn_workspace_bytes"):
+                     "zeda_expert_ffn_workspace_bytes", "zeda_routing_stats_workspace_bytes"):
             getattr(L, name).restype = sz
             getattr(L, name).argtypes = [dp]
         L.zeda_workspace_layout.restype = i32
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.zeda_rmsnorm.argtypes = [i32, i32, i32, vp, vp, ctypes.c_float, vp, vp]
         L.zeda_residual_add.restype = i32
         L.zeda_residual_add.argtypes = [i32, i32, i32, vp, vp, vp]
+        L.zeda_routing_stats.restype = i32
+        L.zeda_routing_stats.argtypes = [dp, vp, vp, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp, sz, vp]
         L.zeda_pack_expert_weights.restype = i32
         L.zeda_pack_expert_weights.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         _lib = L
@@ -190,6 +192,21 @@ def zeda_rmsnorm(x, gamma, eps: float, out, stream=None) -> None:
 def zeda_residual_add(x, y, stream=None) -> None:
     T, H = x.shape
     _check(lib().zeda_residual_add(T, H, _dtype_code(x), _ptr(x), _ptr(y), _stream(stream)), "zeda_residual_add")
+
+
+def zeda_routing_stats(desc, x, w_router, router_bias, alpha=1.0, w=1.0, stream=None):
+    """Section 2.2 statistics over the batch of all tokens; allocates the outputs and the scratch.
+    Returns device tensors (f[N+Z], P[N+Z], summary[7] = f_E, P_E, f_Z, P_Z, r_ZE, L_A, L_GA)."""
+    NE = desc.N + desc.Z
+    f = torch.empty(NE, dtype=torch.float32, device=x.device)
+    P = torch.empty(NE, dtype=torch.float32, device=x.device)
+    summary = torch.empty(7, dtype=torch.float32, device=x.device)
+    nbytes = int(lib().zeda_routing_stats_workspace_bytes(ctypes.byref(desc)))
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
+    _check(lib().zeda_routing_stats(ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(router_bias), float(alpha), float(w),
+                                    _ptr(f), _ptr(P), _ptr(summary), _ptr(ws), ws.numel(), _stream(stream)),
+           "zeda_routing_stats")
+    return f, P, summary
 
 
 def zeda_pack_expert_weights(desc, w_gate, w_up, w_down, stream=None):

@@ -138,6 +138,21 @@ def test_pointer_and_workspace_errors_return_before_any_launch():
     assert lib.zeda_moe_forward_events(dp, ok, ok, None, ok, ok, ok, ok, None, ok, need, None, None) == zeda.ZEDA_EINVAL
 
 
+def test_routing_stats_argument_checks():
+    lib = zeda.lib()
+    d = _desc()
+    ok = ctypes.c_void_p(1 << 20)
+    need = int(lib.zeda_routing_stats_workspace_bytes(ctypes.byref(d)))
+    assert need > 0
+    f32 = ctypes.c_float
+    dp = ctypes.byref(d)
+    assert lib.zeda_routing_stats(dp, ok, ok, None, f32(1), f32(1), ok, ok, ok, ok, need - 1, None) == zeda.ZEDA_EWORKSPACE
+    assert lib.zeda_routing_stats(dp, ok, ok, None, f32(1), f32(0), ok, ok, ok, ok, need, None) == zeda.ZEDA_EINVAL  # w > 0
+    assert lib.zeda_routing_stats(dp, ok, ok, None, f32(1), f32(1), None, ok, ok, ok, need, None) == zeda.ZEDA_EINVAL
+    d0 = _desc(T=0)
+    assert lib.zeda_routing_stats(ctypes.byref(d0), ok, ok, None, f32(1), f32(1), ok, ok, ok, ok, 1 << 30, None) == zeda.ZEDA_EINVAL
+
+
 def test_binding_raises_with_the_status_name():
     d = _desc(K=0)
     with pytest.raises(zeda.ZedaError) as ei:

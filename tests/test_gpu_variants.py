@@ -95,3 +95,34 @@ def test_sequence_length_sweep_ends(T):
     tokens = np.sort(np.random.default_rng(2).choice(w.T, size=128, replace=False))
     res, st = full_parity(w, L, tokens=tokens, tiled=True)
     _say(st)
+
+
+# Batch routing statistics of Section 2.2 (f_i, P_i, group sums, forward values of Eq. 4-6) against the oracle.
+STATS_CASES = [
+    dict(T=1000, H=256, I=64, N=10, Z=6, K=4, dtype="bf16", seed=111, zero_bias=0.3),
+    dict(T=77, H=132, I=52, N=7, Z=5, K=3, dtype="f32", seed=112, zero_bias=0.2),
+    dict(T=300, H=128, I=64, N=9, Z=0, K=2, dtype="bf16", seed=113, zero_bias=0.0),
+    dict(T=5000, H=512, I=64, N=128, Z=64, K=8, dtype="bf16", seed=114, zero_bias=0.3),
+    dict(T=9000, H=128, I=64, N=40, Z=24, K=8, dtype="bf16", seed=115, zero_bias=0.4),  # too many token blocks to split H
+]
+
+
+@pytest.mark.parametrize("cfg", STATS_CASES, ids=lambda c: "T%d_N%d_Z%d_K%d_%s" % (c["T"], c["N"], c["Z"], c["K"], c["dtype"]))
+def test_routing_stats_match_oracle(cfg):
+    w = synth.Workload("stats", recipe="zero_bias", x_std=1.0, w_std=0.05, wr_std=0.05, **cfg)
+    _say("routing stats", w)
+    L = harness.gapped_layer(w, "cuda")
+    alpha, gw = 0.01, 2.0
+    f, P, summ = zeda.zeda_routing_stats(desc_of(w), L["x"], L["w_router"], L["router_bias"], alpha=alpha, w=gw)
+    torch.cuda.synchronize()
+    a = harness.to_arrays(L)
+    ref = orc.routing_stats(a["x"], a["w_router"], a["router_bias"], w.N, w.Z, w.K, alpha=alpha, w=gw)
+    # counts are exact (f = count / T in both; gapped tokens have an unambiguous top-K set)
+    np.testing.assert_allclose(f.cpu().numpy().astype(np.float64), ref["f"], rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(P.cpu().numpy().astype(np.float64), ref["P"], rtol=2e-5, atol=1e-7)
+    got = summ.cpu().numpy().astype(np.float64)
+    want = np.array([ref[k] for k in ("f_E", "P_E", "f_Z", "P_Z", "r_ze", "L_A", "L_GA")])
+    np.testing.assert_allclose(got, want, rtol=2e-5, atol=1e-7)
+    # what the ids of the forward path imply: r_ZE is the share of slots on zero experts
+    res = forward(w, L)
+    assert got[4] == pytest.approx(1.0 - int(res["num_real"].item()) / (w.T * w.K), abs=1e-6)
