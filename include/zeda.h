@@ -189,6 +189,14 @@ typedef struct {
 } zeda_ws_layout;
 int zeda_workspace_layout(const zeda_layer_desc *desc, zeda_ws_layout *layout /* host */);
 
+/* Router rows of the zero experts (Section 2.1, "router initialization"; a model-surgery step, not on the hot
+ * path).  w_router[N+Z, H]: rows 0..N-1 (the post-trained router) are read and kept; rows N..N+Z-1 are written
+ * as mean + std * normals[z, h], mean and (population) variance taken over the N*H original parameters.
+ * normals[Z, H]: fp32 standard-normal draws supplied by the caller (device).  stats (device, may be NULL)
+ * receives {mean, variance} as fp32.  desc->T is ignored.  One workgroup, deterministic. */
+int zeda_init_zero_expert_rows(const zeda_layer_desc *desc, void *w_router, const float *normals, float *stats,
+                               void *stream);
+
 /* Glue of the layer-stack workload x <- x + MoE_l(RMSNorm(x)) (no attention).  Not part of the paper's layer
  * (Appendix D leaves norms and residuals out of its model); used to chain 48 layers with and without zero
  * experts.  x, out, y: [T,H] of `dtype` (zeda_dtype); arithmetic in fp32.

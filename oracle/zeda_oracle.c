@@ -169,6 +169,25 @@ int oracle_routing_stats(const float *x, const float *wr, const float *bias, int
     return 0;
 }
 
+/* Router rows of the Z zero experts (Section 2.1, "router initialization"): the N original rows stay as they
+ * are; the new parameters are Gaussian with the mean and the (population) variance of the N*H original router
+ * parameters.  The standard-normal draws are an input (normals[Z,H]), so that both sides of a parity test use
+ * the same ones: rows[z,h] = mean + std * normals[z,h].  stats (may be NULL) receives {mean, variance}. */
+int oracle_init_zero_rows(const float *wr, const float *normals, int N, int Z, int H, double *rows, double *stats)
+{
+    if (N < 1 || Z < 0 || H < 1) return -1;
+    const size_t n = (size_t)N * H;
+    double mean = 0.0, var = 0.0;
+    for (size_t i = 0; i < n; ++i) mean += (double)wr[i];
+    mean /= (double)n;
+    for (size_t i = 0; i < n; ++i) var += ((double)wr[i] - mean) * ((double)wr[i] - mean);
+    var /= (double)n;
+    const double sd = sqrt(var);
+    for (size_t i = 0; i < (size_t)Z * H; ++i) rows[i] = mean + sd * (double)normals[i];
+    if (stats) { stats[0] = mean; stats[1] = var; }
+    return 0;
+}
+
 /* One normal expert on one token (Appendix D: gate, up and down projections; SwiGLU reading):
  * y = W_down ( silu(W_gate h) * (W_up h) ).  act is scratch of I doubles. */
 static void expert_apply(const float *xt, const float *wg, const float *wu, const float *wd, int H, int I,

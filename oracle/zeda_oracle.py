@@ -172,6 +172,21 @@ def routing_stats(x, w_router, router_bias, N: int, Z: int, K: int, alpha: float
     return {"f": f, "P": P, **{k: float(v) for k, v in zip(keys, summ)}}
 
 
+def init_zero_rows(w_router_normal, normals):
+    """Section 2.1, router initialisation: rows[Z,H] = mean + std * normals, (mean, variance) of the N*H originals."""
+    lib = _load()
+    wr = _f32(w_router_normal)
+    N, H = wr.shape
+    z = _f32(normals)
+    Z = z.shape[0]
+    assert z.shape == (Z, H)
+    rows = np.empty((Z, H), dtype=np.float64)
+    stats = np.empty(2, dtype=np.float64)
+    if lib.oracle_init_zero_rows(_p(wr), _p(z), N, Z, H, _p(rows), _p(stats)) != 0:
+        raise ValueError("oracle_init_zero_rows: bad arguments")
+    return rows, float(stats[0]), float(stats[1])
+
+
 def moe_flops(n, H, He, N, NZ, K, r_ze) -> float:
     return float(_load().oracle_moe_flops(n, H, He, N, NZ, K, r_ze))
 

@@ -24,7 +24,8 @@ STAGES = ("route", "dispatch", "gateup", "down", "combine")
 EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_route_workspace_bytes", "zeda_dispatch_workspace_bytes",
            "zeda_expert_ffn_workspace_bytes", "zeda_workspace_layout", "zeda_route", "zeda_dispatch",
            "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events", "zeda_rmsnorm",
-           "zeda_residual_add", "zeda_pack_expert_weights", "zeda_routing_stats_workspace_bytes", "zeda_routing_stats")
+           "zeda_residual_add", "zeda_pack_expert_weights", "zeda_routing_stats_workspace_bytes", "zeda_routing_stats",
+           "zeda_init_zero_expert_rows")
 
 
 class LayerDesc(ctypes.Structure):
@@ -82,6 +83,8 @@ def lib() -> ctypes.CDLL:
         L.zeda_residual_add.argtypes = [i32, i32, i32, vp, vp, vp]
         L.zeda_routing_stats.restype = i32
         L.zeda_routing_stats.argtypes = [dp, vp, vp, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp, sz, vp]
+        L.zeda_init_zero_expert_rows.restype = i32
+        L.zeda_init_zero_expert_rows.argtypes = [dp, vp, vp, vp, vp]
         L.zeda_pack_expert_weights.restype = i32
         L.zeda_pack_expert_weights.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         _lib = L
@@ -207,6 +210,14 @@ def zeda_routing_stats(desc, x, w_router, router_bias, alpha=1.0, w=1.0, stream=
                                     _ptr(f), _ptr(P), _ptr(summary), _ptr(ws), ws.numel(), _stream(stream)),
            "zeda_routing_stats")
     return f, P, summary
+
+
+def zeda_init_zero_expert_rows(desc, w_router, normals, stream=None):
+    """Fills rows N.. of w_router in place (see include/zeda.h); returns the device tensor {mean, variance}."""
+    stats = torch.empty(2, dtype=torch.float32, device=w_router.device)
+    _check(lib().zeda_init_zero_expert_rows(ctypes.byref(desc), _ptr(w_router), _ptr(normals), _ptr(stats), _stream(stream)),
+           "zeda_init_zero_expert_rows")
+    return stats
 
 
 def zeda_pack_expert_weights(desc, w_gate, w_up, w_down, stream=None):

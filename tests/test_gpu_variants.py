@@ -126,3 +126,25 @@ def test_routing_stats_match_oracle(cfg):
     # what the ids of the forward path imply: r_ZE is the share of slots on zero experts
     res = forward(w, L)
     assert got[4] == pytest.approx(1.0 - int(res["num_real"].item()) / (w.T * w.K), abs=1e-6)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_zero_expert_router_rows_initialisation(dtype):
+    # Section 2.1: new router rows are Gaussian with the mean and variance of the original router parameters
+    N, Z, H = 24, 8, 256
+    g = torch.Generator().manual_seed(3)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    wr = torch.empty((N + Z, H), dtype=tdt)
+    wr[:N] = (0.1 + 0.02 * torch.randn((N, H), generator=g)).to(tdt)
+    wr[N:] = float("nan")
+    z = torch.randn((Z, H), generator=g, dtype=torch.float32)
+    d = zeda.make_desc(1, H, 64, N, Z, 2, dtype)
+    dev = wr.cuda()
+    stats = zeda.zeda_init_zero_expert_rows(d, dev, z.cuda())
+    torch.cuda.synchronize()
+    rows, mean, var = orc.init_zero_rows(wr[:N].float().numpy(), z.numpy())
+    got = dev.float().cpu().numpy()
+    assert np.array_equal(got[:N], wr[:N].float().numpy())  # the original rows are untouched
+    np.testing.assert_allclose(stats.cpu().numpy(), [mean, var], rtol=1e-6)
+    tol = 2.0 ** -8 if dtype == "bf16" else 1e-6  # one rounding of the result to the element type
+    np.testing.assert_allclose(got[N:], rows, rtol=tol, atol=1e-7)

@@ -373,3 +373,30 @@ def test_routing_stats_bias_moves_slots_to_the_zero_group():
     assert s["f_Z"] == pytest.approx(K) and s["r_ze"] == pytest.approx(1.0) and s["P_Z"] > 1 - 1e-9
     with pytest.raises(ValueError):
         orc.routing_stats(L["x"], L["wr"], None, N, Z, K, w=0.0)
+
+
+# ----------------------------------------------------------------------------------------------
+# Router rows of the zero experts (Section 2.1, router initialisation)
+# ----------------------------------------------------------------------------------------------
+def test_zero_expert_row_initialisation():
+    r = np.random.default_rng(71)
+    N, Z, H = 9, 5, 40
+    wr = (0.3 + 0.05 * r.standard_normal((N, H))).astype(np.float32)
+    z = r.standard_normal((Z, H)).astype(np.float32)
+    rows, mean, var = orc.init_zero_rows(wr, z)
+    # the library routines on the same numbers
+    assert mean == pytest.approx(np.mean(wr.astype(np.float64)), rel=1e-13)
+    assert var == pytest.approx(np.var(wr.astype(np.float64)), rel=1e-12)
+    np.testing.assert_allclose(rows, mean + math.sqrt(var) * z.astype(np.float64), rtol=1e-14)
+    # equal original parameters: no spread, every new parameter is that value
+    rows, mean, var = orc.init_zero_rows(np.full((N, H), 0.25, dtype=np.float32), z)
+    assert var == 0.0 and np.all(rows == 0.25)
+    # +a / -a in equal numbers: mean 0, standard deviation a, so the new rows are a * (the draws)
+    pm = np.where((np.arange(N * H) % 2) == 0, 0.5, -0.5).astype(np.float32).reshape(N, H)
+    rows, mean, var = orc.init_zero_rows(pm, z)
+    assert mean == 0.0 and var == 0.25
+    np.testing.assert_array_equal(rows, 0.5 * z.astype(np.float64))
+    # many draws: the new parameters have the mean and the variance of the old ones (sampling error ~ 1/sqrt(n))
+    rows, mean, var = orc.init_zero_rows(wr, r.standard_normal((2000, H)).astype(np.float32))
+    assert np.mean(rows) == pytest.approx(mean, abs=4 * math.sqrt(var / rows.size))
+    assert np.var(rows) == pytest.approx(var, rel=0.03)
