@@ -74,7 +74,7 @@ def run_layer(w: synth.Workload, L, steps: int, warmup: int):
 
 
 def stack_bench(a) -> int:
-    """BASELINE config 5: time the chained stack at Z=32 and at Z=0 (same weights, router restricted to the
+    """benchmark configuration 5: time the chained stack at Z=32 and at Z=0 (same weights, router restricted to the
     normal experts); one step = one pass of all layers over T=8192 tokens."""
     from paper_2605_18643_amd.stack import MoeStack
 

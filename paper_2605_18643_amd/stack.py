@@ -1,4 +1,4 @@
-"""The layer-stack workload: L MoE layers chained as x <- x + MoE_l(RMSNorm(x)), no attention (BASELINE
+"""The layer-stack workload: L MoE layers chained as x <- x + MoE_l(RMSNorm(x)), no attention (benchmark
 config 5).  This file only owns buffers and the order of the C-ABI calls; every step runs in the HIP library."""
 from __future__ import annotations
 

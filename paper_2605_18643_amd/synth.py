@@ -191,22 +191,22 @@ NZ64_ZERO_BIAS = 0.2991
 GLM_LIKE_ZERO_BIAS = 0.3092
 
 CONFIGS: Dict[str, Workload] = {
-    # BASELINE config 1: tiny fp32 layer, no bias, seed 0.
+    # benchmark configuration 1: tiny fp32 layer, no bias, seed 0.
     "c1_tiny_f32": Workload("c1_tiny_f32", T=64, H=256, I=128, N=8, Z=4, K=2, dtype="f32", seed=0,
                             recipe="plain", x_std=0.02, w_std=0.02, wr_std=0.05),
-    # BASELINE config 2: Qwen3-30B-A3B-shaped prefill layer, ~4 of 8 slots on zero experts.
+    # benchmark configuration 2: Qwen3-30B-A3B-shaped prefill layer, ~4 of 8 slots on zero experts.
     "c2_qwen_prefill": Workload("c2_qwen_prefill", T=4096, H=2048, I=768, N=128, Z=32, K=8, dtype="bf16",
                                 seed=1, recipe="zero_bias", zero_bias=QWEN_ZERO_BIAS),
-    # BASELINE config 3: the same layer in a decode shape.
+    # benchmark configuration 3: the same layer in a decode shape.
     "c3_qwen_decode": Workload("c3_qwen_decode", T=64, H=2048, I=768, N=128, Z=32, K=8, dtype="bf16",
                                seed=2, recipe="zero_bias", zero_bias=QWEN_ZERO_BIAS),
-    # BASELINE config 4: heterogeneous difficulty + Zipf(1.1) expert popularity.
+    # benchmark configuration 4: heterogeneous difficulty + Zipf(1.1) expert popularity.
     "c4_hetero_prefill": Workload("c4_hetero_prefill", T=16384, H=2048, I=768, N=128, Z=32, K=8, dtype="bf16",
                                   seed=3, recipe="planted"),
-    # BASELINE config 5: one layer of the 48-layer stack (T=8192); layer l uses seed 4000 + l.
+    # benchmark configuration 5: one layer of the 48-layer stack (T=8192); layer l uses seed 4000 + l.
     "c5_stack_layer": Workload("c5_stack_layer", T=8192, H=2048, I=768, N=128, Z=32, K=8, dtype="bf16",
                                seed=4000, recipe="zero_bias", zero_bias=QWEN_ZERO_BIAS),
-    # Further workloads (not in the benchmark spec).  The paper's own zero-expert count on the Qwen3 shape (App. D
+    # Further workloads (beyond the five benchmark configurations).  The paper's own zero-expert count on the Qwen3 shape (App. D
     # Table 12: N_Z = 64), prefill and its decode concurrency of 32 ...
     "n1_qwen_nz64_prefill": Workload("n1_qwen_nz64_prefill", T=4096, H=2048, I=768, N=128, Z=64, K=8, dtype="bf16",
                                      seed=11, recipe="zero_bias", zero_bias=NZ64_ZERO_BIAS),

@@ -1,4 +1,4 @@
-"""GPU parity at the full BASELINE sizes, in the launch configuration bench.py times.
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
 Routing and dispatch are checked on every token; the oracle's expert arithmetic runs on all tokens where it
 finishes in seconds (configs 2 and 3) and on a sample of tokens at T=16384 (config 4)."""
 import numpy as np

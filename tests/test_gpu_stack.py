@@ -1,4 +1,4 @@
-"""BASELINE config 5: a chain of MoE layers with RMSNorm + residual between them (no attention).
+"""benchmark configuration 5: a chain of MoE layers with RMSNorm + residual between them (no attention).
 
 Inputs of layers >= 1 cannot be re-drawn to keep a logit gap, so each checked layer is teacher-forced: the
 oracle gets the GPU's own normalised input of that layer, routing is compared on the tokens whose oracle gap is
