@@ -60,3 +60,17 @@ def test_config4_hetero_prefill_sampled():
     load = np.diff(res["expert_offsets"].numpy())
     _say("rows per expert: max", load.max(), "min", load.min(), "empty", int((load == 0).sum()))
     assert load.max() > 8 * load.mean()
+
+
+def test_maximum_slot_count():
+    # T*K just under the 2^24 limit of the interface (16.7 M slots, several GB of intermediates): the indices,
+    # offsets and the permutation are checked on every slot, the arithmetic on sampled tokens
+    w = synth.Workload("max_slots", T=2_097_000, H=128, I=64, N=6, Z=2, K=8, dtype="bf16", seed=7, recipe="zero_bias",
+                       x_std=1.0, w_std=0.05, wr_std=0.05, zero_bias=0.1)
+    assert w.T * w.K < (1 << 24)
+    _say("maximum slot count", w)
+    L = harness.gapped_layer(w, "cuda")
+    tokens = np.sort(np.random.default_rng(3).choice(w.T, size=256, replace=False))
+    res, st = full_parity(w, L, tokens=tokens, tiled=True)
+    _say(st)
+    assert st["R"] > (1 << 23)
