@@ -91,3 +91,27 @@ def test_forward_is_deterministic():
     R = int(a["num_real"].item())
     assert torch.equal(a["sorted_slot"][:R], b["sorted_slot"][:R])
     assert torch.equal(a["y_slot"][:R].view(torch.int16), b["y_slot"][:R].view(torch.int16))
+
+
+def test_empty_batch_is_a_no_op_on_every_entry_point():
+    # T = 0: nothing is launched that could touch memory; dispatch still publishes all-zero offsets
+    w = synth.Workload("empty", T=0, H=128, I=64, N=5, Z=3, K=2, dtype="bf16", seed=1, recipe="plain")
+    d = zeda.make_desc(0, w.H, w.I, w.N, w.Z, w.K, "bf16")
+    L = synth.make_layer(w.with_(T=4), "cuda")
+    x0 = L["x"]  # any valid pointer: no row of it is read (a NULL pointer would be an argument error even at T = 0)
+    guard = torch.full((8, w.H), 7.0, dtype=torch.bfloat16, device="cuda")  # a buffer that must stay untouched
+    ws = torch.empty(max(zeda.workspace_bytes(d), 256), dtype=torch.uint8, device="cuda")
+    nreal = torch.full((1,), -3, dtype=torch.int32, device="cuda")
+    zeda.zeda_moe_forward(d, x0, L["w_router"], None, L["w_gate"], L["w_up"], L["w_down"], guard, nreal, ws)
+    ids = torch.full((4,), -9, dtype=torch.int32, device="cuda")
+    gates = torch.full((4,), -9.0, dtype=torch.float32, device="cuda")
+    zeda.zeda_route(d, x0, L["w_router"], None, ids, gates)
+    off = torch.full((w.N + 1,), -5, dtype=torch.int32, device="cuda")
+    ss = torch.full((4,), -5, dtype=torch.int32, device="cuda")
+    s2r = torch.full((4,), -5, dtype=torch.int32, device="cuda")
+    nr = torch.full((1,), -5, dtype=torch.int32, device="cuda")
+    zeda.zeda_dispatch(d, ids, off, ss, s2r, nr, ws)
+    zeda.zeda_combine(d, guard, ids, gates, s2r, guard)
+    torch.cuda.synchronize()
+    assert (guard.float() == 7.0).all() and (ids == -9).all() and (gates == -9.0).all()
+    assert not off.cpu().numpy().any() and int(nr.item()) == 0 and (ss == -5).all() and (s2r == -5).all()
