@@ -206,6 +206,21 @@ int zeda_init_zero_expert_rows(const zeda_layer_desc *desc, void *w_router, cons
 int zeda_rmsnorm(int32_t T, int32_t H, int32_t dtype, const void *x, const void *gamma, float eps, void *out, void *stream);
 int zeda_residual_add(int32_t T, int32_t H, int32_t dtype, void *x, const void *y, void *stream);
 
+/* One pre-norm residual block of that chain in a single call: the layer of Eq. 1 (Section 2.1) applied to the
+ * normalised input xn, with the weighted sum of Eq. 1 added straight into the residual stream,
+ *   x_res[t,:] <- x_res[t,:] + sum_i g~_i E_i(xn[t,:])          (in place, rounded to the element type)
+ *   xn_next[t,:] = RMSNorm(x_res[t,:]) * gamma_next             (of the stored row; skipped if xn_next is NULL)
+ * so that the combine stage replaces zeda_combine + zeda_residual_add + the next layer's zeda_rmsnorm.  The sum
+ * is added in fp32 before the one rounding, i.e. without the intermediate rounding of a separate layer output.
+ * All other arguments, the workspace and the stage order are those of zeda_moe_forward.  xn, x_res, xn_next:
+ * [T,H] device; xn_next may be the same buffer as xn (each row is read before it is written); x_res must be
+ * distinct from both.  gamma_next[H] device or NULL (= 1).  H <= 8192 (bf16) / 4096 (fp32), else
+ * ZEDA_EUNSUPPORTED.  ZEDA_EINVAL on NULL / unaligned pointers, eps < 0, or x_res aliasing xn or xn_next. */
+int zeda_moe_block_forward(const zeda_layer_desc *desc, const void *xn, void *x_res, const void *w_router,
+                           const float *router_bias, const void *w_gate, const void *w_up, const void *w_down,
+                           const void *gamma_next, float eps, void *xn_next, int32_t *num_real_out, void *ws,
+                           size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

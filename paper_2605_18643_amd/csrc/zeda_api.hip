@@ -52,16 +52,33 @@ static void layout_of(const zeda_layer_desc *d, zeda_ws_layout *L)
     L->total = o;
 }
 
+// Tail of the pre-norm residual block variant: the combine adds into x_res and writes the next layer's input.
+struct BlockTail {
+    void *x_res;
+    const void *gamma;
+    float eps;
+    void *xn_next;
+};
+
+// out: the layer output, or NULL when tail is given
 static int forward_impl(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,
                         const void *w_gate, const void *w_up, const void *w_down, void *out, int32_t *num_real_out,
-                        void *ws, size_t ws_bytes, void *stream, void *const *events)
+                        void *ws, size_t ws_bytes, void *stream, void *const *events, const BlockTail *tail = nullptr)
 {
     int rc = check_desc(desc);
     if (rc != ZEDA_OK) return rc;
-    if (!x || !w_router || !w_gate || !w_up || !w_down || !out || !ws) return ZEDA_EINVAL;
+    if (!x || !w_router || !w_gate || !w_up || !w_down || !ws) return ZEDA_EINVAL;
     if (!aligned16(x) || !aligned16(w_router) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) ||
-        !aligned16(out) || !aligned16(ws) || (router_bias && !aligned16(router_bias)))
+        !aligned16(ws) || (router_bias && !aligned16(router_bias)))
         return ZEDA_EINVAL;
+    if (tail) {
+        if (!tail->x_res || !aligned16(tail->x_res) || !aligned16(tail->gamma) || !aligned16(tail->xn_next) ||
+            !(tail->eps >= 0.f) || tail->x_res == x || tail->x_res == tail->xn_next)
+            return ZEDA_EINVAL;
+        if (!combine_block_supported(desc)) return ZEDA_EUNSUPPORTED;
+    } else if (!out || !aligned16(out)) {
+        return ZEDA_EINVAL;
+    }
     zeda_ws_layout L;
     layout_of(desc, &L);
     if (ws_bytes < L.total) return ZEDA_EWORKSPACE;
@@ -93,7 +110,10 @@ static int forward_impl(const zeda_layer_desc *desc, const void *x, const void *
     mark(1 + ZEDA_STAGE_GATEUP);
     if ((rc = launch_down(desc, act, w_down, offsets, y_slot, s)) != ZEDA_OK) return rc;
     mark(1 + ZEDA_STAGE_DOWN);
-    if ((rc = launch_combine(desc, y_slot, ids, gates, slot_to_row, x, out, s)) != ZEDA_OK) return rc;
+    rc = tail ? launch_combine_block(desc, y_slot, ids, gates, slot_to_row, x, tail->x_res, tail->gamma, tail->eps,
+                                     tail->xn_next, s)
+              : launch_combine(desc, y_slot, ids, gates, slot_to_row, x, out, s);
+    if (rc != ZEDA_OK) return rc;
     mark(1 + ZEDA_STAGE_COMBINE);
     return rc;
 }
@@ -231,6 +251,16 @@ int zeda_moe_forward_events(const zeda_layer_desc *desc, const void *x, const vo
         if (!events[i]) return ZEDA_EINVAL;
     return forward_impl(desc, x, w_router, router_bias, w_gate, w_up, w_down, out, num_real_out, ws, ws_bytes, stream,
                         events);
+}
+
+int zeda_moe_block_forward(const zeda_layer_desc *desc, const void *xn, void *x_res, const void *w_router,
+                           const float *router_bias, const void *w_gate, const void *w_up, const void *w_down,
+                           const void *gamma_next, float eps, void *xn_next, int32_t *num_real_out, void *ws,
+                           size_t ws_bytes, void *stream)
+{
+    const BlockTail tail = {x_res, gamma_next, eps, xn_next};
+    return forward_impl(desc, xn, w_router, router_bias, w_gate, w_up, w_down, nullptr, num_real_out, ws, ws_bytes,
+                        stream, nullptr, &tail);
 }
 
 size_t zeda_routing_stats_workspace_bytes(const zeda_layer_desc *desc)

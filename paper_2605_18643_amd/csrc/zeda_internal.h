@@ -45,6 +45,12 @@ int launch_pack_weights(const zeda_layer_desc *d, const void *w, void *out, bool
 int launch_combine(const zeda_layer_desc *d, const void *y_slot, const int32_t *ids, const float *gates,
                    const int32_t *slot_to_row, const void *x, void *out, hipStream_t s);
 
+// combine fused with the pre-norm residual block: x_res += MoE output; xn_next (may be NULL) = RMSNorm(x_res) * gamma
+bool combine_block_supported(const zeda_layer_desc *d);
+int launch_combine_block(const zeda_layer_desc *d, const void *y_slot, const int32_t *ids, const float *gates,
+                         const int32_t *slot_to_row, const void *x, void *x_res, const void *gamma, float eps,
+                         void *xn_next, hipStream_t s);
+
 inline int last_launch_status() { return hipGetLastError() == hipSuccess ? ZEDA_OK : ZEDA_EHIP; }
 
 }  // namespace zeda

@@ -35,9 +35,28 @@ class MoeStack:
         self.y = torch.empty((ww.T, ww.H), dtype=ww.torch_dtype, device=device)
         self.num_real = torch.zeros(layers, dtype=torch.int32, device=device)
 
-    def forward(self, x: torch.Tensor, hook=None) -> torch.Tensor:
-        """Runs the chain in place on x (the residual stream) and returns it.  hook(l, stack) is called after
-        layer l's MoE output is in self.y and before the residual add (the stream is not synchronised)."""
+    def forward(self, x: torch.Tensor, hook=None, fused: Optional[bool] = None) -> torch.Tensor:
+        """Runs the chain in place on x (the residual stream) and returns it.  The stream is never synchronised.
+        fused (default: whenever no hook is given): one zeda_moe_block_forward per layer, whose combine stage adds
+        into x and writes the next layer's normalised input; one RMSNorm kernel for the first layer only.
+        hook(l, stack, x) is then called before layer l (self.xn is its input, x the stream so far) and once more
+        with l = layers after the last one.
+        Otherwise three calls per layer, and hook(l, stack) is called after layer l's MoE output is in self.y and
+        before the residual add."""
+        if fused is None:
+            fused = hook is None
+        if fused:
+            zeda.zeda_rmsnorm(x, None, EPS, self.xn)
+            for l, p in enumerate(self.weights):
+                if hook is not None:
+                    hook(l, self, x)
+                last = l == self.layers - 1
+                zeda.zeda_moe_block_forward(self.desc, self.xn, x, p["w_router"], p["router_bias"], p["w_gate"],
+                                            p["w_up"], p["w_down"], None, EPS, None if last else self.xn,
+                                            self.num_real[l: l + 1], self.ws)
+            if hook is not None:
+                hook(self.layers, self, x)
+            return x
         for l, p in enumerate(self.weights):
             zeda.zeda_rmsnorm(x, None, EPS, self.xn)
             zeda.zeda_moe_forward(self.desc, self.xn, p["w_router"], p["router_bias"], p["w_gate"], p["w_up"], p["w_down"],

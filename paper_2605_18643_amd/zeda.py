@@ -23,7 +23,8 @@ STAGES = ("route", "dispatch", "gateup", "down", "combine")
 
 EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_route_workspace_bytes", "zeda_dispatch_workspace_bytes",
            "zeda_expert_ffn_workspace_bytes", "zeda_workspace_layout", "zeda_route", "zeda_dispatch",
-           "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events", "zeda_rmsnorm",
+           "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events", "zeda_moe_block_forward",
+           "zeda_rmsnorm",
            "zeda_residual_add", "zeda_pack_expert_weights", "zeda_routing_stats_workspace_bytes", "zeda_routing_stats",
            "zeda_init_zero_expert_rows")
 
@@ -77,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.zeda_moe_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.zeda_moe_forward_events.restype = i32
         L.zeda_moe_forward_events.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(vp)]
+        L.zeda_moe_block_forward.restype = i32
+        L.zeda_moe_block_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
         L.zeda_rmsnorm.restype = i32
         L.zeda_rmsnorm.argtypes = [i32, i32, i32, vp, vp, ctypes.c_float, vp, vp]
         L.zeda_residual_add.restype = i32
@@ -180,6 +183,15 @@ def zeda_moe_forward_events(desc, x, w_router, router_bias, w_gate, w_up, w_down
                                          _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(num_real_out),
                                          _ptr(ws), ws.numel() * ws.element_size(), _stream(stream), arr),
            "zeda_moe_forward_events")
+
+
+def zeda_moe_block_forward(desc, xn, x_res, w_router, router_bias, w_gate, w_up, w_down, gamma_next, eps: float,
+                           xn_next, num_real_out, ws, stream=None) -> None:
+    """x_res += layer(xn) in place; xn_next (None to skip, may be xn itself) = RMSNorm(x_res) * gamma_next."""
+    _check(lib().zeda_moe_block_forward(ctypes.byref(desc), _ptr(xn), _ptr(x_res), _ptr(w_router), _ptr(router_bias),
+                                        _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(gamma_next), float(eps),
+                                        _ptr(xn_next), _ptr(num_real_out), _ptr(ws), ws.numel() * ws.element_size(),
+                                        _stream(stream)), "zeda_moe_block_forward")
 
 
 def _dtype_code(t: torch.Tensor) -> int:

@@ -138,6 +138,27 @@ def test_pointer_and_workspace_errors_return_before_any_launch():
     assert lib.zeda_moe_forward_events(dp, ok, ok, None, ok, ok, ok, ok, None, ok, need, None, None) == zeda.ZEDA_EINVAL
 
 
+def test_block_forward_argument_checks():
+    lib = zeda.lib()
+    d = _desc()
+    dp = ctypes.byref(d)
+    ok, ok2, ok3 = (ctypes.c_void_p(v << 20) for v in (1, 2, 3))
+    odd = ctypes.c_void_p((1 << 20) + 8)
+    need = zeda.workspace_bytes(d)
+    eps = ctypes.c_float(1e-6)
+    call = lib.zeda_moe_block_forward
+    assert call(dp, ok, None, ok, None, ok, ok, ok, None, eps, ok3, None, ok, need, None) == zeda.ZEDA_EINVAL
+    assert call(dp, ok, odd, ok, None, ok, ok, ok, None, eps, ok3, None, ok, need, None) == zeda.ZEDA_EINVAL
+    assert call(dp, ok, ok, ok, None, ok, ok, ok, None, eps, ok3, None, ok, need, None) == zeda.ZEDA_EINVAL  # x_res is xn
+    assert call(dp, ok, ok2, ok, None, ok, ok, ok, None, eps, ok2, None, ok, need, None) == zeda.ZEDA_EINVAL  # x_res is xn_next
+    assert call(dp, ok, ok2, ok, None, ok, ok, ok, None, ctypes.c_float(-1), ok3, None, ok, need, None) == zeda.ZEDA_EINVAL
+    assert call(dp, ok, ok2, ok, None, ok, ok, ok, odd, eps, ok3, None, ok, need, None) == zeda.ZEDA_EINVAL
+    assert call(dp, ok, ok2, ok, None, ok, ok, ok, None, eps, ok3, None, ok, need - 1, None) == zeda.ZEDA_EWORKSPACE
+    wide = _desc(H=8192 + 128)
+    assert zeda.workspace_bytes(wide) > 0
+    assert call(ctypes.byref(wide), ok, ok2, ok, None, ok, ok, ok, None, eps, ok3, None, ok, 1 << 40, None) == zeda.ZEDA_EUNSUPPORTED
+
+
 def test_routing_stats_argument_checks():
     lib = zeda.lib()
     d = _desc()

@@ -36,7 +36,85 @@ def test_rmsnorm_and_residual_kernels():
         assert torch.equal(x, want)
 
 
-def test_tiny_fp32_stack_end_to_end():
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("copy_expert", [False, True])
+def test_block_forward_against_the_oracle(dtype, copy_expert):
+    # one pre-norm residual block in one call: x_res += layer(xn), xn_next = RMSNorm(x_res) * gamma
+    w = synth.Workload("block", T=333, H=256, I=128, N=8, Z=4, K=3, dtype=dtype, seed=77, recipe="zero_bias",
+                       x_std=1.0, w_std=0.06, wr_std=0.2, zero_bias=0.2)
+    _say("block forward:", w, "copy expert" if copy_expert else "zero expert")
+    xn = synth.draw_tokens(w, "cuda")
+    wr, bias = synth.draw_router(w, "cuda")
+    wg, wu, wd = synth.draw_experts(w, "cuda")
+    g = torch.Generator().manual_seed(5)
+    x_res0 = (torch.randn(w.T, w.H, generator=g) * 2.0).to(w.torch_dtype).cuda()
+    gamma = (torch.rand(w.H, generator=g) + 0.5).to(w.torch_dtype).cuda()
+    desc = zeda.make_desc(w.T, w.H, w.I, w.N, w.Z, w.K, w.dtype,
+                          free_expert=zeda.EXPERT_COPY if copy_expert else zeda.EXPERT_ZERO)
+    ws = torch.empty(zeda.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    nreal = torch.zeros(1, dtype=torch.int32, device="cuda")
+    x_res, xn_next = x_res0.clone(), torch.empty_like(xn)
+    zeda.zeda_moe_block_forward(desc, xn, x_res, wr, bias, wg, wu, wd, gamma, EPS, xn_next, nreal, ws)
+    torch.cuda.synchronize()
+    a = [synth.to_numpy_f32(v) for v in (xn, wr, bias, wg, wu, wd)]
+    r = orc.moe_forward(*a, w.N, w.Z, w.K, copy_expert=copy_expert)
+    assert np.array_equal(zeda.ws_views(desc, ws)["topk_ids"].cpu().numpy(), r["ids"])
+    assert int(nreal.item()) == int((r["ids"] < w.N).sum())
+    want = x_res0.double().cpu().numpy() + r["out"]
+    got = x_res.double().cpu().numpy()
+    # one rounding of the sum to the element type, on top of the expert arithmetic's own error
+    step = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -23
+    assert np.max(np.abs(got - want)) <= step * np.max(np.abs(want)) + (2e-2 if dtype == "bf16" else 1e-5)
+    assert harness.rel_l2(got, want) < (1e-2 if dtype == "bf16" else 1e-5)
+    # the norm is taken of the row as stored
+    ref_n = orc.rmsnorm(synth.to_numpy_f32(x_res), synth.to_numpy_f32(gamma), EPS)
+    tol = 6e-3 if dtype == "bf16" else 2e-6
+    np.testing.assert_allclose(xn_next.float().cpu().numpy(), ref_n, rtol=tol, atol=tol * 1e-2)
+    # the three-call form gives the same stream up to the extra rounding of its separate layer output
+    y = torch.empty_like(xn)
+    zeda.zeda_moe_forward(desc, xn, wr, bias, wg, wu, wd, y, nreal, ws)
+    x3 = x_res0.clone()
+    zeda.zeda_residual_add(x3, y)
+    torch.cuda.synchronize()
+    assert harness.rel_l2(x3.double().cpu().numpy(), got) < (4e-3 if dtype == "bf16" else 1e-6)
+    # no next input wanted; and the next input written over the layer's own input
+    x_b = x_res0.clone()
+    zeda.zeda_moe_block_forward(desc, xn, x_b, wr, bias, wg, wu, wd, None, EPS, None, nreal, ws)
+    xn_io = xn.clone()
+    x_c = x_res0.clone()
+    zeda.zeda_moe_block_forward(desc, xn_io, x_c, wr, bias, wg, wu, wd, gamma, EPS, xn_io, nreal, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(x_b, x_res) and torch.equal(x_c, x_res) and torch.equal(xn_io, xn_next)
+
+
+def test_block_forward_rows_wider_than_one_pass():
+    # H / 8 > 256: a thread keeps several pieces of the row between the add and the norm
+    w = synth.Workload("block_wide", T=70, H=2048 + 512, I=64, N=4, Z=2, K=2, dtype="bf16", seed=78, recipe="zero_bias",
+                       x_std=1.0, w_std=0.03, wr_std=0.05, zero_bias=0.2)
+    _say("block forward, wide rows:", w)
+    xn = synth.draw_tokens(w, "cuda")
+    wr, bias = synth.draw_router(w, "cuda")
+    wg, wu, wd = synth.draw_experts(w, "cuda")
+    x_res0 = torch.randn(w.T, w.H, generator=torch.Generator().manual_seed(6)).to(w.torch_dtype).cuda()
+    desc = zeda.make_desc(w.T, w.H, w.I, w.N, w.Z, w.K, w.dtype)
+    ws = torch.empty(zeda.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    nreal = torch.zeros(1, dtype=torch.int32, device="cuda")
+    x_res, xn_next = x_res0.clone(), torch.empty_like(xn)
+    zeda.zeda_moe_block_forward(desc, xn, x_res, wr, bias, wg, wu, wd, None, EPS, xn_next, nreal, ws)
+    torch.cuda.synchronize()
+    r = orc.moe_forward(*[synth.to_numpy_f32(v) for v in (xn, wr, bias, wg, wu, wd)], w.N, w.Z, w.K)
+    want = x_res0.double().cpu().numpy() + r["out"]
+    assert harness.rel_l2(x_res.double().cpu().numpy(), want) < 1e-2
+    np.testing.assert_allclose(xn_next.float().cpu().numpy(), orc.rmsnorm(synth.to_numpy_f32(x_res), None, EPS),
+                               rtol=6e-3, atol=6e-5)
+    too_wide = zeda.make_desc(8, 8192 + 128, 64, 4, 2, 2, "bf16")
+    with pytest.raises(zeda.ZedaError) as ei:
+        zeda.zeda_moe_block_forward(too_wide, xn, x_res, wr, bias, wg, wu, wd, None, EPS, None, nreal, ws)
+    assert ei.value.status == zeda.ZEDA_EUNSUPPORTED
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_tiny_fp32_stack_end_to_end(fused):
     # four small fp32 layers: the whole chain against the oracle chain (routing compared where unambiguous)
     w = synth.Workload("tiny_stack", T=96, H=128, I=64, N=8, Z=4, K=2, dtype="f32", seed=900, recipe="zero_bias",
                        x_std=1.0, w_std=0.08, wr_std=0.2, zero_bias=0.1)
@@ -44,7 +122,10 @@ def test_tiny_fp32_stack_end_to_end():
     x = synth.draw_tokens(w, "cuda")
     ref = x.double().cpu().numpy()
     ids_gpu = []
-    out = st.forward(x.clone(), hook=lambda l, s: ids_gpu.append(zeda.ws_views(s.desc, s.ws)["topk_ids"].clone()))
+    if fused:  # no hook in the one-call-per-layer chain: routing is then only checked through the final stream
+        out = st.forward(x.clone())
+    else:
+        out = st.forward(x.clone(), hook=lambda l, s: ids_gpu.append(zeda.ws_views(s.desc, s.ws)["topk_ids"].clone()))
     torch.cuda.synchronize()
     excluded = 0
     for l, p in enumerate(st.weights):
@@ -54,7 +135,8 @@ def test_tiny_fp32_stack_end_to_end():
         _, _, lg = orc.route(xn, a["w_router"], a["router_bias"], w.N, w.Z, w.K, want_logits=True)
         safe = harness.topk_gaps(lg, w.K) >= harness.GAP
         excluded += int((~safe).sum())
-        assert np.array_equal(ids_gpu[l].cpu().numpy()[safe], r["ids"][safe])
+        if not fused:
+            assert np.array_equal(ids_gpu[l].cpu().numpy()[safe], r["ids"][safe])
         ref = ref + r["out"]
     _say("tokens excluded from the routing comparison over 4 layers:", excluded)
     got = out.double().cpu().numpy()
@@ -100,6 +182,57 @@ def test_config5_stack_teacher_forced():
         rl2, mabs = check_float(w, y.float().cpu().numpy()[tok], r["out"], f"layer {l} output")
         _say(f"layer {l}: {int((~safe).sum())} of {w.T} tokens excluded from the routing comparison; "
              f"sampled output rel-L2 {rl2:.2e} max-abs {mabs:.2e}; r_ZE {1 - nreal[l] / (w.T * w.K):.3f}")
+    assert np.isfinite(x.float().cpu().numpy()).all()
+
+
+def test_config5_fused_chain_teacher_forced():
+    # the one-call-per-layer chain at full size: for each checked layer the oracle gets the GPU's own normalised
+    # input and stream, and must reproduce the routing, the dispatch, the new stream rows and the next input
+    w = synth.CONFIGS["c5_stack_layer"]
+    layers = 48
+    _say("config 5, fused blocks:", w, "layers", layers)
+    st = MoeStack(w, layers, tiled=True)
+    x = synth.draw_tokens(w, "cuda")
+    check = (0, 1, 23, 47)
+    before, after = {}, {}
+
+    def hook(l, s, xs):
+        if l - 1 in check:  # layer l-1 has run: its routing tables, the new stream and the next layer's input
+            v = zeda.ws_views(s.desc, s.ws)
+            after[l - 1] = (xs.clone(), s.xn.clone(), v["topk_ids"].clone(), v["expert_offsets"].clone())
+        if l in check:
+            before[l] = (xs.clone(), s.xn.clone())
+
+    st.forward(x, hook=hook, fused=True)
+    torch.cuda.synchronize()
+    nreal = st.num_real.cpu().numpy()
+    assert 0.35 < (1 - nreal / (w.T * w.K)).mean() < 0.65
+    rng = np.random.default_rng(6)
+    for l in check:
+        x0, xn = before[l]
+        x1, xn1, ids, off = after[l]
+        a = {k: synth.to_numpy_f32(v) for k, v in st.weights[l].items() if k in ("w_router", "router_bias")}
+        wg, wu, wd = synth.draw_experts(w, "cuda", l)  # the stack holds them tiled: the oracle wants them row-major
+        xn_h = synth.to_numpy_f32(xn)
+        rid, _, lg = orc.route(xn_h, a["w_router"], a["router_bias"], w.N, w.Z, w.K, want_logits=True)
+        safe = harness.topk_gaps(lg, w.K) >= harness.GAP
+        ids_h = ids.cpu().numpy()
+        assert np.array_equal(ids_h[safe], rid[safe]), f"layer {l}"
+        roff, _, _ = orc.dispatch(ids_h, w.N)
+        assert np.array_equal(off.cpu().numpy(), roff)
+        tok = np.sort(rng.choice(np.flatnonzero(safe), size=96, replace=False))
+        r = orc.moe_forward(xn_h[tok], a["w_router"], a["router_bias"], *[synth.to_numpy_f32(v) for v in (wg, wu, wd)],
+                            w.N, w.Z, w.K)
+        want = x0.double().cpu().numpy()[tok] + r["out"]
+        got = x1.double().cpu().numpy()[tok]
+        rl2, mabs = harness.rel_l2(got, want), float(np.max(np.abs(got - want)))
+        # the expert arithmetic's tolerance plus the one bf16 rounding of the stream row
+        assert rl2 < 1e-2 and mabs <= 2e-2 + 2.0 ** -8 * float(np.max(np.abs(want))), (l, rl2, mabs)
+        if l + 1 < layers:
+            np.testing.assert_allclose(synth.to_numpy_f32(xn1)[tok], orc.rmsnorm(synth.to_numpy_f32(x1)[tok], None, EPS),
+                                       rtol=6e-3, atol=6e-5)
+        _say(f"layer {l}: {int((~safe).sum())} of {w.T} tokens excluded from the routing comparison; "
+             f"sampled stream rows rel-L2 {rl2:.2e} max-abs {mabs:.2e}; r_ZE {1 - nreal[l] / (w.T * w.K):.3f}")
     assert np.isfinite(x.float().cpu().numpy()).all()
 
 
