@@ -112,6 +112,14 @@ __device__ __forceinline__ u32x4 lds_read_b128(uint32_t a)
     asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(a) : "memory");
     return v;
 }
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read_b128_at(uint32_t a)  // a + OFF, the constant in the instruction's offset field
+{
+    static_assert(OFF >= 0 && OFF < 65536, "16-bit offset field");
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(a), "n"(OFF) : "memory");
+    return v;
+}
 __device__ __forceinline__ void lds_write_b64(uint32_t a, u32x2 v)
 {
     asm volatile("ds_write_b64 %0, %1" ::"v"(a), "v"(v) : "memory");
@@ -186,6 +194,7 @@ struct Stream {
     int Kdim, Fdim, nk;
     // LDS
     unsigned char *wring, *tring, *stg;
+    uint32_t wring_a, tring_a;  // LDS addresses of the two rings
     const int *s_tok;
     const int4 *s_loc;
     // thread position
@@ -197,6 +206,9 @@ struct Stream {
     bool wrole;
     const bf16_t *src[NLMAX];
     int nq, iq, ikc, islot, inl;
+    size_t koff;          // ikc chunks into the rows, in elements
+    int kstep;            // elements from one chunk of this wave's operand to the next
+    uint32_t dbase, doff; // LDS address of this wave's first piece in slot 0 of its ring; byte offset of slot islot
     int hist[NH];  // load instructions of this wave in each of the last chunks issued (newest last)
     // compute side: slots of the chunk being multiplied
     int cslot_w, cslot_t;
@@ -258,15 +270,44 @@ struct Stream {
             }
         }
     }
+    __device__ __forceinline__ void init_issue()
+    {
+        wring_a = lds_addr(wring);
+        tring_a = lds_addr(tring);
+        kstep = (TILED && wrole) ? (Fdim / 32) * 1024 : KC;
+        dbase = lds_addr(wrole ? wring + wave * 1024 : tring + (wave - NWW) * 1024);
+        iq = 0; ikc = 0; islot = 0; inl = 0; koff = 0; doff = 0;
+#pragma unroll
+        for (int h = 0; h < NH; ++h) hist[h] = 0;
+    }
+    __device__ __forceinline__ void load_piece(int i)
+    {
+        const uint32_t dst = dbase + doff + i * ((NWW == NWT ? NWW : (wrole ? NWW : NWT)) * 1024);
+        __builtin_amdgcn_global_load_lds(ZEDA_GLOBAL_PTR(src[i] + koff),
+                                         (__attribute__((address_space(3))) void *)(uintptr_t)dst, 16, 0, 0);
+    }
+    // the issue position moves on by one chunk inside the current item
+    __device__ __forceinline__ void next_chunk_same_item()
+    {
+        ++ikc;
+        koff += kstep;
+        const bool wrap = ++islot == (NSW == NST ? NSW : (wrole ? NSW : NST));
+        doff = wrap ? 0 : doff + (WST == TST ? WST : (wrole ? WST : TST));
+        islot = wrap ? 0 : islot;
+    }
     // load instruction i of the chunk being issued (i < ni, wave-uniform)
     __device__ __forceinline__ void issue_one(int i, int ni)
     {
-        if (i < ni) {
-            const int step = (TILED && wrole) ? (Fdim / 32) * 1024 : KC;  // elements from one chunk to the next
-            unsigned char *dst = wrole ? wring + islot * WST + (wave + NWW * i) * 1024
-                                       : tring + islot * TST + (wave - NWW + NWT * i) * 1024;
-            __builtin_amdgcn_global_load_lds(ZEDA_GLOBAL_PTR(src[i] + (size_t)ikc * step), ZEDA_LDS_PTR(dst), 16, 0, 0);
-        }
+        if (i < ni) load_piece(i);
+    }
+    // the same when the chunk belongs to an item with GA live groups and the stream has not ended: the count is known
+    template <int GA>
+    __device__ __forceinline__ void issue_one_of(int i)
+    {
+        constexpr int NT = C::nlt(GA);
+        if (i < NLW && i < NT) load_piece(i);
+        else if (i < NLW) { if (wrole) load_piece(i); }
+        else if (i < NT) { if (!wrole) load_piece(i); }
     }
     // bookkeeping after the instructions of one chunk were issued (ni of them; 0 once the stream has ended)
     __device__ __forceinline__ void issued(int ni)
@@ -275,12 +316,18 @@ struct Stream {
         for (int h = 0; h + 1 < NH; ++h) hist[h] = hist[h + 1];
         hist[NH - 1] = ni;
         if (iq < nq) {
-            islot = islot + 1 == (wrole ? NSW : NST) ? 0 : islot + 1;
-            if (++ikc == nk) {
-                ikc = 0;
-                ++iq;
-                setup_issue_item();
-            }
+            next_chunk_same_item();
+            next_item_if_done();
+        }
+    }
+    // past the last chunk of the item: the next chunk to fetch is the first one of the next item
+    __device__ __forceinline__ void next_item_if_done()
+    {
+        if (ikc == nk) {
+            ikc = 0;
+            koff = 0;
+            ++iq;
+            setup_issue_item();
         }
     }
     __device__ __forceinline__ void issue_burst()
@@ -304,15 +351,95 @@ struct Stream {
     // Fragments of k step s of the chunk in `slot`: FB weight blocks of this wave column, GA token blocks of this
     // wave row.  Blocks start at multiples of 32 rows, so the piece permutation depends on `col` only and the
     // address is one per-lane term (foff, XOR 32*s) plus block offsets that are immediates.
-    template <int GA>
-    __device__ __forceinline__ void load_frags(const unsigned char *wslot, const unsigned char *tslot, int s,
-                                               bf16x8 (&fa)[FB], bf16x8 (&tb)[GA]) const
+    // The reads go around the compiler (see the LDS helpers above) so that the wait before a step's MFMAs can be a
+    // counted one: it leaves the reads of the step after it, issued just before, in flight.
+    template <int I, int N, int STRIDE>
+    static __device__ __forceinline__ void read_blocks(uint32_t base, u32x4 *out)
     {
-        const unsigned char *pw = wslot + (foff_w ^ (s << 5)), *pt = tslot + (foff_t ^ (s << 5));
+        if constexpr (I < N) {
+            out[I] = lds_read_b128_at<I * STRIDE>(base);
+            read_blocks<I + 1, N, STRIDE>(base, out);
+        }
+    }
+    // wslot, tslot: LDS addresses of the chunk's weight and token slot
+    template <int GA>
+    __device__ __forceinline__ void load_frags(uint32_t wslot, uint32_t tslot, int s, u32x4 (&fa)[FB], u32x4 (&tb)[GA]) const
+    {
+        read_blocks<0, FB, 32 * ROWB>(wslot + (foff_w ^ (s << 5)), fa);
+        read_blocks<0, GA, 64 * ROWB>(tslot + (foff_t ^ (s << 5)), tb);
+    }
+    // the fragments in fa, tb have landed when at most `newer` LDS reads issued after them are still in flight
+    template <int NEWER, int GA>
+    __device__ __forceinline__ void frags_landed(u32x4 (&fa)[FB], u32x4 (&tb)[GA]) const
+    {
+        asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(NEWER) : "memory");
 #pragma unroll
-        for (int b = 0; b < FB; ++b) fa[b] = *reinterpret_cast<const bf16x8 *>(pw + b * 32 * ROWB);
+        for (int b = 0; b < FB; ++b) asm volatile("" : "+v"(fa[b]));
 #pragma unroll
-        for (int a = 0; a < GA; ++a) tb[a] = *reinterpret_cast<const bf16x8 *>(pt + a * 64 * ROWB);
+        for (int a = 0; a < GA; ++a) asm volatile("" : "+v"(tb[a]));
+    }
+
+    // One chunk of an item with GA live groups: KS k steps; in the last one the next chunk is awaited, everybody
+    // meets, and the slot everybody has left is refilled.  MAIN: all loads in flight are this item's (see tile_body).
+    template <int GA, bool MAIN>
+    __device__ __forceinline__ void chunk(f32x16 (&acc)[GA][FB], u32x4 (&fa)[2][FB], u32x4 (&tb)[2][GA], bool more)
+    {
+        const uint32_t cur_w = wring_a + cslot_w * WST, cur_t = tring_a + cslot_t * TST;
+        const int nslot_w = cslot_w + 1 == NSW ? 0 : cslot_w + 1, nslot_t = cslot_t + 1 == NST ? 0 : cslot_t + 1;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int p = s & 1;
+            int ni = 0;
+            if (s < KS - 1) {
+                load_frags<GA>(cur_w, cur_t, s + 1, fa[p ^ 1], tb[p ^ 1]);
+                frags_landed<FB + GA, GA>(fa[p], tb[p]);
+            } else {
+                // every fragment of this chunk is in registers: nobody needs its slot any more
+                frags_landed<0, GA>(fa[p], tb[p]);
+                // Wait for the next chunk, meet, refill the slot everybody has just left.  After the item's last
+                // chunk the next chunk is the first one of the next item (nothing, at the end of the stream): it is
+                // awaited HERE, before the epilogue, because the epilogue's stores count in vmcnt too - a wait
+                // right after them would have to sit out their whole round trip.
+                if (MAIN) {
+                    constexpr int WW = (NSW - 2) * NLW, WT_ = (NST - 2) * C::nlt(GA);
+                    if (WW == WT_) wait_vmcnt<WW>();
+                    else if (wrole) wait_vmcnt<WW>();
+                    else wait_vmcnt<WT_>();
+                } else {
+                    wait_oldest();
+                }
+                __builtin_amdgcn_s_barrier();
+                if (MAIN || more) load_frags<GA>(wring_a + nslot_w * WST, tring_a + nslot_t * TST, 0, fa[p ^ 1], tb[p ^ 1]);
+                ni = inl;
+            }
+            // keep the reads of the next step ahead of this step's MFMAs
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int a = 0; a < GA; ++a)
+#pragma unroll
+                for (int b = 0; b < FB; ++b) {
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[p][b]),
+                                                                        __builtin_bit_cast(bf16x8, tb[p][a]), acc[a][b], 0, 0, 0);
+                    if (s == KS - 1) {
+                        // the refill of the slot freed by the barrier, spread over this step's MFMAs
+                        constexpr int NM = GA * FB;
+                        const int m = a * FB + b;
+#pragma unroll
+                        for (int i = 0; i < NLMAX; ++i)
+                            if (i * NM / NLMAX == m) {
+                                if (MAIN) issue_one_of<GA>(i);
+                                else issue_one(i, ni);
+                            }
+                    }
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            if (s == KS - 1) {
+                if (MAIN) next_chunk_same_item();
+                else issued(ni);
+            }
+        }
+        cslot_w = nslot_w;
+        cslot_t = nslot_t;
     }
 
     // One item with GA live 64-row groups: its nk chunks, then the epilogue.
@@ -329,53 +456,22 @@ struct Stream {
 
         // On entry the item's first chunk has landed and everybody has met after waiting for it (the item before,
         // or the start of the stream, saw to that).
-        bf16x8 fa[2][FB], tb[2][GA];
-        load_frags<GA>(wring + cslot_w * WST, tring + cslot_t * TST, 0, fa[0], tb[0]);
+        u32x4 fa[2][FB], tb[2][GA];
+        load_frags<GA>(wring_a + cslot_w * WST, tring_a + cslot_t * TST, 0, fa[0], tb[0]);
 
-        for (int kc = 0; kc < nk; ++kc) {
-            const unsigned char *cur_w = wring + cslot_w * WST, *cur_t = tring + cslot_t * TST;
-            const int nslot_w = cslot_w + 1 == NSW ? 0 : cslot_w + 1, nslot_t = cslot_t + 1 == NST ? 0 : cslot_t + 1;
-            const bool more = kc + 1 < nk;
+        // Main part: the chunks during which every load in flight belongs to this item, so that the number of loads
+        // that may stay outstanding at the wait is a constant of the item's shape (an immediate).  The last chunks,
+        // during which the first chunks of the next item are fetched, take the counted path.
+        constexpr int NSMAX = NSW > NST ? NSW : NST;
+        const int n_main = nk > NSMAX ? nk - NSMAX : 0;  // chunk kc refills with chunk kc + depth: still this item's
+        int kc = 0;
+        for (; kc < n_main; ++kc) chunk<GA, true>(acc, fa, tb, true);
+        if (n_main > 0) {
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                const int p = s & 1;
-                int ni = 0;
-                if (s < KS - 1) {
-                    load_frags<GA>(cur_w, cur_t, s + 1, fa[p ^ 1], tb[p ^ 1]);
-                } else {
-                    // every fragment of this chunk is in registers: nobody needs its slot any more
-                    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-                    // Wait for the next chunk, meet, refill the slot everybody has just left.  After the item's last
-                    // chunk the next chunk is the first one of the next item (nothing, at the end of the stream): it is
-                    // awaited HERE, before the epilogue, because the epilogue's stores count in vmcnt too - a wait
-                    // right after them would have to sit out their whole round trip.
-                    wait_oldest();
-                    __builtin_amdgcn_s_barrier();
-                    if (more) load_frags<GA>(wring + nslot_w * WST, tring + nslot_t * TST, 0, fa[p ^ 1], tb[p ^ 1]);
-                    ni = inl;
-                }
-                // keep the reads of the next step ahead of this step's MFMAs
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int a = 0; a < GA; ++a)
-#pragma unroll
-                    for (int b = 0; b < FB; ++b) {
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[p][b], tb[p][a], acc[a][b], 0, 0, 0);
-                        if (s == KS - 1) {
-                            // the refill of the slot freed by the barrier, spread over this step's MFMAs
-                            constexpr int NM = GA * FB;
-                            const int m = a * FB + b;
-#pragma unroll
-                            for (int i = 0; i < NLMAX; ++i)
-                                if (i * NM / NLMAX == m) issue_one(i, ni);
-                        }
-                    }
-                __builtin_amdgcn_sched_barrier(0);
-                if (s == KS - 1) issued(ni);
-            }
-            cslot_w = nslot_w;
-            cslot_t = nslot_t;
+            for (int h = 0; h < NH; ++h) hist[h] = wrole ? NLW : C::nlt(GA);
+            next_item_if_done();  // (the deeper ring's last refill there was the item's last chunk)
         }
+        for (; kc < nk; ++kc) chunk<GA, false>(acc, fa, tb, kc + 1 < nk);
 
         // Epilogue.  acc[a][b][v] is feature 8*(v/4) + 4*half + v%4 of weight block b, token `col` of token
         // block 2a + wt.  Each 32x32 result block goes through this wave's LDS buffer (rows of 32 bf16, pieces
@@ -498,9 +594,8 @@ __global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__re
         st.foff_t = (st.wt * 32 + st.col) * C::ROWB + swz<C::KC>(st.col, st.half) * 16;
         st.foff_w = (st.wf * C::FB * 32 + st.col) * C::ROWB + swz<C::KC>(st.col, st.half) * 16;
         st.wrole = wave < C::NWW;
-        st.nq = nq; st.iq = 0; st.ikc = 0; st.islot = 0; st.cslot_w = 0; st.cslot_t = 0; st.inl = 0;
-#pragma unroll
-        for (int h = 0; h < Stream<C, GATEUP, TILED>::NH; ++h) st.hist[h] = 0;
+        st.nq = nq; st.cslot_w = 0; st.cslot_t = 0;
+        st.init_issue();
         st.setup_issue_item();
         for (int c = 0, n = (st.wrole ? C::NSW : C::NST) - 1; c < n; ++c) st.issue_burst();
         // all slots of this wave's ring but one are in flight: wait for the first chunk, meet, fill the last slot
