@@ -111,8 +111,9 @@ def stack_bench(a) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default 1000 for one layer, 50 for the 48-layer stack)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default 200 / 5)")
     ap.add_argument("--workload", default="c2_qwen_prefill", choices=sorted(synth.CONFIGS) + ["c5_stack"],
                     help="c5_stack: the 48-layer chain (RMSNorm + residual, no attention) with and without zero experts")
     ap.add_argument("--layers", type=int, default=48)
@@ -125,6 +126,13 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-z0", action="store_true")
     a = ap.parse_args()
+    # A short run measures the first milliseconds after idle, before the clocks have settled: the default covers
+    # about a third of a second of sustained work (the stack's steps are 25 ms each, so 50 of them do).
+    stack = a.workload == "c5_stack"
+    if a.steps is None:
+        a.steps = 50 if stack else 1000
+    if a.warmup is None:
+        a.warmup = 5 if stack else 200
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (no collectives, no sharding); "
               "run it with --gpus 1", file=sys.stderr)
