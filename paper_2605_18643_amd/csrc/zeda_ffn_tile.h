@@ -74,7 +74,12 @@ __device__ __forceinline__ int swz(int row, int piece)
     return KC == 64 ? (piece ^ ((row >> 1) & 7)) : (piece ^ ((row >> 2) & 3));
 }
 
-__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.f + __expf(-g)) * u; }
+// silu(g) * u with the hardware reciprocal (1 ulp) in place of an IEEE division: the result is rounded to bf16
+// right after, and the division sequence was a quarter of the gate/up epilogue's instructions
+__device__ __forceinline__ float silu_mul(float g, float u)
+{
+    return g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * u;
+}
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
