@@ -22,9 +22,12 @@
 // last chunks of an item are multiplied and its result is written, the first chunks of the next item are
 // already in flight, so HBM never sees the pipeline drain between tiles.  Per chunk there is one counted
 // s_waitcnt (this wave's own loads of that chunk) and one s_barrier (everybody's loads have landed, and
-// everybody has left the slots that are refilled next).  The refill is issued a few instructions at a
+// everybody has left the slots that are refilled next).  While all loads in flight belong to the item being
+// multiplied the count is a constant of the item's shape; only an item's last chunks, during which the next
+// item's first chunks are fetched, count what is in flight.  The refill is issued a few instructions at a
 // time between the MFMAs that follow the barrier, so that the texture path never sees all waves issue at
-// once; fragments are double-buffered in registers and read one k step ahead.
+// once; fragments are double-buffered in registers and read one k step ahead, and a step's MFMAs wait only
+// for the fragment reads issued a whole step earlier.
 //
 // Only the 64-row groups of a token tile that hold rows are fetched and multiplied (their number is a
 // template parameter of the tile body, so the MFMA loop has no branches), and the two wave rows take

@@ -99,3 +99,21 @@ def test_config3_decode_full_tiled():
     L = harness.gapped_layer(w, "cuda")
     res, st = full_parity(w, L, tiled=True)
     _say(st)
+
+
+# The GEMM loop treats the chunks of an item differently depending on whether the loads in flight all belong to
+# the item (its first chunks) or reach into the next item (its last `ring depth` chunks): widths whose chunk
+# counts fall below, at and just above the ring depth, for both k-chunk widths (32 tiled, 64 row-major), with
+# enough rows per expert for several items per workgroup and a ragged last tile.
+CHUNK_EDGE_WIDTHS = [(128, 64), (128, 128), (256, 64), (256, 192), (384, 320), (640, 128)]
+
+
+@pytest.mark.parametrize("tiled", [False, True], ids=["row_major", "tiled"])
+@pytest.mark.parametrize("H, I", CHUNK_EDGE_WIDTHS, ids=lambda v: str(v))
+def test_chunk_counts_around_the_ring_depth(H, I, tiled):
+    w = synth.Workload("chunk_edges", T=700, H=H, I=I, N=3, Z=2, K=2, dtype="bf16", seed=86 + H + I, recipe="zero_bias",
+                       x_std=1.0, w_std=0.05, wr_std=0.05, zero_bias=0.2)
+    _say("chunk edges", "tiled" if tiled else "row-major", w)
+    L = harness.gapped_layer(w, "cuda")
+    res, st = full_parity(w, L, tiled=tiled)
+    assert st["R"] > 0 and np.isfinite(res["out"].float().numpy()).all()
