@@ -33,5 +33,15 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def device_isa(source: str, out_path: str) -> str:
+    """Device-side ISA text (hipcc -S) of one of SOURCES, for lds_wait_check."""
+    cmd = ["hipcc", *FLAGS, "-S", "--cuda-device-only", os.path.join(CSRC, source), "-o", out_path]
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        sys.stderr.write(proc.stderr)
+        raise RuntimeError(f"hipcc -S failed on {source}")
+    return out_path
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

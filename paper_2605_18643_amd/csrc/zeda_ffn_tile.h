@@ -389,8 +389,9 @@ struct Stream {
 
     // One chunk of an item with GA live groups: KS k steps; in the last one the next chunk is awaited, everybody
     // meets, and the slot everybody has left is refilled.  MAIN: all loads in flight are this item's (see tile_body).
-    template <int GA, bool MAIN>
-    __device__ __forceinline__ void chunk(f32x16 (&acc)[GA][FB], u32x4 (&fa)[2][FB], u32x4 (&tb)[2][GA], bool more)
+    // MORE: the item has another chunk after this one (its first fragments are read here, after the meeting).
+    template <int GA, bool MAIN, bool MORE>
+    __device__ __forceinline__ void chunk(f32x16 (&acc)[GA][FB], u32x4 (&fa)[2][FB], u32x4 (&tb)[2][GA])
     {
         const uint32_t cur_w = wring_a + cslot_w * WST, cur_t = tring_a + cslot_t * TST;
         const int nslot_w = cslot_w + 1 == NSW ? 0 : cslot_w + 1, nslot_t = cslot_t + 1 == NST ? 0 : cslot_t + 1;
@@ -417,7 +418,7 @@ struct Stream {
                     wait_oldest();
                 }
                 __builtin_amdgcn_s_barrier();
-                if (MAIN || more) load_frags<GA>(wring_a + nslot_w * WST, tring_a + nslot_t * TST, 0, fa[p ^ 1], tb[p ^ 1]);
+                if (MORE) load_frags<GA>(wring_a + nslot_w * WST, tring_a + nslot_t * TST, 0, fa[p ^ 1], tb[p ^ 1]);
                 ni = inl;
             }
             // keep the reads of the next step ahead of this step's MFMAs
@@ -473,13 +474,14 @@ struct Stream {
         constexpr int NSMAX = NSW > NST ? NSW : NST;
         const int n_main = nk > NSMAX ? nk - NSMAX : 0;  // chunk kc refills with chunk kc + depth: still this item's
         int kc = 0;
-        for (; kc < n_main; ++kc) chunk<GA, true>(acc, fa, tb, true);
+        for (; kc < n_main; ++kc) chunk<GA, true, true>(acc, fa, tb);
         if (n_main > 0) {
 #pragma unroll
             for (int h = 0; h < NH; ++h) hist[h] = wrole ? NLW : C::nlt(GA);
             next_item_if_done();  // (the deeper ring's last refill there was the item's last chunk)
         }
-        for (; kc < nk; ++kc) chunk<GA, false>(acc, fa, tb, kc + 1 < nk);
+        for (; kc + 1 < nk; ++kc) chunk<GA, false, true>(acc, fa, tb);
+        chunk<GA, false, false>(acc, fa, tb);
 
         // Epilogue.  acc[a][b][v] is feature 8*(v/4) + 4*half + v%4 of weight block b, token `col` of token
         // block 2a + wt.  Each 32x32 result block goes through this wave's LDS buffer (rows of 32 bf16, pieces
