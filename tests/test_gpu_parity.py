@@ -50,6 +50,10 @@ SMALL_BF16 = [
     dict(T=20, H=256, I=128, N=12, Z=4, K=4, seed=15, zero_bias=0.4),
     dict(T=64, H=256, I=128, N=12, Z=4, K=4, seed=16, zero_bias=0.4),
     dict(T=1, H=256, I=128, N=12, Z=4, K=4, seed=17, zero_bias=0.4),
+    # a single normal expert next to zero experts (every real slot in one group, one long run of token tiles)
+    dict(T=700, H=128, I=64, N=1, Z=3, K=2, seed=18, zero_bias=0.1),
+    # every expert selected by every token (K = N + Z): routing only orders them
+    dict(T=90, H=128, I=64, N=3, Z=2, K=5, seed=19, zero_bias=0.1),
 ]
 
 
