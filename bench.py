@@ -125,6 +125,9 @@ def main() -> int:
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters; outside the timed region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-z0", action="store_true")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="context: also time torch.bmm (the vendor GEMM library) on dense batched GEMMs of the expert "
+                         "GEMMs' shapes (no gather, no SwiGLU, every expert with the mean row count)")
     a = ap.parse_args()
     # A short run measures the first milliseconds after idle, before the clocks have settled: the default covers
     # about a third of a second of sustained work (the stack's steps are 25 ms each, so 50 of them do).
@@ -215,6 +218,27 @@ def main() -> int:
         res["z0"] = {"ms_per_step": r0["wall_s"] / a.steps * 1e3, "speedup_vs_z0": r0["wall_s"] / r["wall_s"],
                      "real_slots": r0["R"], "expert_flop_reduction": 1.0 - R / max(1, r0["R"]),
                      "stage_us": {k: float(v) * 1e3 for k, v in zip(zeda.STAGES, r0["stage_ms"])}}
+
+    if a.library_gemm and w.dtype == "bf16" and ne > 0:
+        # What the vendor's batched GEMM reaches on this machine for the same amount of matrix work, in the same kind
+        # of sustained loop: a yardstick for the MFMA-bound workloads (the nominal peak is not reached by it either).
+        m = max(1, -(-R // ne))
+        lib = {}
+        for name, (kd, nd) in (("gateup", (w.H, 2 * w.I)), ("down", (w.I, w.H))):
+            A = torch.randn(ne, m, kd, device="cuda", dtype=torch.bfloat16)
+            B = torch.randn(ne, kd, nd, device="cuda", dtype=torch.bfloat16) * 0.02
+            C = torch.empty(ne, m, nd, device="cuda", dtype=torch.bfloat16)
+            for _ in range(50):
+                torch.bmm(A, B, out=C)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(200):
+                torch.bmm(A, B, out=C)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / 200
+            lib[name] = {"us": dt * 1e6, "tflops": 2.0 * ne * m * kd * nd / dt / 1e12, "batch": ne, "rows": m}
+            del A, B, C
+        res["library_gemm"] = lib
 
     if not a.no_cpu_baseline:
         from oracle import harness, zeda_oracle as orc  # CPU-baseline leg only
