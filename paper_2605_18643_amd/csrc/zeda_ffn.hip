@@ -93,6 +93,10 @@ typedef TileCfg<1, 2, 2, 4, 4, 32> CfgDecode;   // 64 tokens x 128 weight rows, 
 // tiled weights come in 32-wide k blocks: 32-wide chunks, four deep
 typedef TileCfg<4, 2, 4, 4, 4, 32> CfgPrefillT;
 typedef TileCfg<4, 2, 2, 4, 4, 32> CfgNarrowT;
+// 320 tokens x 256 weight rows (token ring three deep): an expert with up to 320 rows is one token tile, so the
+// experts that CfgPrefillT would give a second, nearly empty tile stream their weights once.  It is the second
+// geometry of the adaptive kernel, which picks one of the two from the expert loads.
+typedef TileCfg<5, 2, 4, 4, 3, 32> CfgPrefillT5;
 
 // Persistent grid: as many workgroups as the device holds at once, rounded down to a multiple of 8 so that
 // every XCD gets the same number (the kernel reads the count from gridDim).
@@ -112,6 +116,39 @@ static int resident_grid()
         grid = g > 0 ? g : 8;
     }
     return grid;
+}
+
+template <class CA, class CB, bool GATEUP, bool TILED>
+static int launch_adaptive_kernel(const zeda_layer_desc *d, const void *tok, const void *w0, const void *w1,
+                                  const int32_t *offsets, const int32_t *sorted_slot, void *out, hipStream_t s)
+{
+    constexpr int kLds = CA::LDS_BYTES > CB::LDS_BYTES ? CA::LDS_BYTES : CB::LDS_BYTES;
+    auto kern = ffn_bf16_adaptive_kernel<CA, CB, GATEUP, TILED>;
+    static int grid = 0;  // (as in resident_grid)
+    if (grid == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kern, CA::THREADS, kLds) != hipSuccess)
+            return ZEDA_EHIP;
+        const int g = cus * (per_cu > 0 ? per_cu : 1) / 8 * 8;
+        grid = g > 0 ? g : 8;
+    }
+    const int Kdim = GATEUP ? d->H : d->I, Fdim = GATEUP ? d->I : d->H;
+    const int n_ftiles = GATEUP ? Fdim / (CA::BF / 2) : Fdim / CA::BF;
+    kern<<<grid, CA::THREADS, kLds, s>>>((const bf16_t *)tok, (const bf16_t *)w0, (const bf16_t *)w1, offsets, sorted_slot,
+                                         (bf16_t *)out, d->N, d->K, Kdim, Fdim, n_ftiles, d->T);
+    return last_launch_status();
+}
+
+// Whether the expert loads may sit just above the 256-row tile (the adaptive kernel then decides on the device; where
+// they cannot, the plain kernel saves the 1-2 % the second geometry costs the first).  The mean row count is T*K/N
+// when every slot is real and anything below that with zero experts.
+static bool rows_may_straddle_tile(const zeda_layer_desc *d)
+{
+    const double all_real = (double)d->T * d->K / d->N;
+    return d->Z == 0 ? (all_real > 240.0 && all_real <= 330.0) : (all_real > 256.0 && all_real < 1024.0);
 }
 
 template <class C, bool GATEUP, bool TILED>
@@ -143,8 +180,11 @@ static int launch_bf16(const zeda_layer_desc *d, const void *tok, const void *w0
     const bool decode = d->T <= CfgDecode::BT && cfg_fits<CfgDecode>(d);
     if (d->weight_layout == ZEDA_WEIGHTS_TILED) {
         if (decode) return launch_tile_kernel<CfgDecode, GATEUP, true>(d, tok, w0, w1, offsets, sorted_slot, out, s);
-        if (cfg_fits<CfgPrefillT>(d))
+        if (cfg_fits<CfgPrefillT>(d)) {
+            if (rows_may_straddle_tile(d))
+                return launch_adaptive_kernel<CfgPrefillT, CfgPrefillT5, GATEUP, true>(d, tok, w0, w1, offsets, sorted_slot, out, s);
             return launch_tile_kernel<CfgPrefillT, GATEUP, true>(d, tok, w0, w1, offsets, sorted_slot, out, s);
+        }
         return launch_tile_kernel<CfgNarrowT, GATEUP, true>(d, tok, w0, w1, offsets, sorted_slot, out, s);
     }
     if (decode) return launch_tile_kernel<CfgDecode, GATEUP, false>(d, tok, w0, w1, offsets, sorted_slot, out, s);

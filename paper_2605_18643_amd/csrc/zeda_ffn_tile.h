@@ -58,6 +58,10 @@ struct TileCfg {
     static constexpr int nlt(int g) { return 64 * g / RPI / NWT; }  // ... of a token wave with g live 64-row groups
     static constexpr int NLMAX = NLW > nlt(G) ? NLW : nlt(G);
     static constexpr int MAXQ = 8;                // items looked up at a time
+    // Token tiles of an expert with m rows: one tile while they fit, else tiles of at most 256 rows (a tile wider
+    // than 256 rows only pays where it saves a second pass over the expert's weights).
+    static constexpr int SPLIT = BT < 256 ? BT : 256;
+    static __host__ __device__ constexpr int tiles_of(int m) { return m <= BT ? (m > 0 ? 1 : 0) : (m + SPLIT - 1) / SPLIT; }
     static constexpr int TRING_OFF = WRING;
     static constexpr int TOK_OFF = WRING + TRING;            // int32 [MAXQ][BT]: source row of every tile row
     static constexpr int LOC_OFF = TOK_OFF + MAXQ * BT * 4;  // int4  [MAXQ]: expert, row0, rows, feature tile
@@ -142,18 +146,27 @@ __device__ __forceinline__ void lds_wait(u32x4 &a, u32x4 &b) { asm volatile("s_w
 #define ZEDA_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
 // Per-lane view of expert_offsets: lane l holds experts 4l..4l+3, their tile counts and the running total.
-template <int BT>
+template <class C>
 struct TileScan {
     int off[5], nt[4], incl, local, tiles;
     __device__ __forceinline__ void init(const int32_t *__restrict__ offsets, int N)
     {
         const int lane = threadIdx.x & 63;
+        int o[5];
 #pragma unroll
-        for (int q = 0; q < 5; ++q) off[q] = offsets[min(4 * lane + q, N)];
+        for (int q = 0; q < 5; ++q) o[q] = offsets[min(4 * lane + q, N)];
+        init(o);
+    }
+    // from this lane's five offsets, already loaded
+    __device__ __forceinline__ void init(const int (&o)[5])
+    {
+        const int lane = threadIdx.x & 63;
+#pragma unroll
+        for (int q = 0; q < 5; ++q) off[q] = o[q];
         local = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            nt[q] = (off[q + 1] - off[q] + BT - 1) / BT;
+            nt[q] = C::tiles_of(off[q + 1] - off[q]);
             local += nt[q];
         }
         incl = local;
@@ -549,16 +562,13 @@ struct TileDispatch<C, GATEUP, TILED, 0> {
 // Kdim is a multiple of KC; Fdim a multiple of the feature tile (BF/2 for GATEUP, BF for DOWN).
 // TILED: the weights are in the layout pack_weights_kernel writes.  The grid is a multiple of 8 workgroups.
 template <class C, bool GATEUP, bool TILED>
-__global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__restrict__ tok,
-                                                              const bf16_t *__restrict__ w0,
-                                                              const bf16_t *__restrict__ w1,
-                                                              const int32_t *__restrict__ offsets,
-                                                              const int32_t *__restrict__ sorted_slot,
-                                                              bf16_t *__restrict__ out, int N, int K, int Kdim, int Fdim,
-                                                              int n_ftiles, int T)
+__device__ __forceinline__ void run_tiles(unsigned char *lds, const TileScan<C> &scan0, const bf16_t *__restrict__ tok,
+                                          const bf16_t *__restrict__ w0,
+                                          const bf16_t *__restrict__ w1, const int32_t *__restrict__ offsets,
+                                          const int32_t *__restrict__ sorted_slot, bf16_t *__restrict__ out, int N, int K,
+                                          int Kdim, int Fdim, int n_ftiles, int T)
 {
     static_assert(!GATEUP || C::FB % 2 == 0, "gate and up blocks come in pairs");
-    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     int *s_tok = reinterpret_cast<int *>(lds + C::TOK_OFF);
     int4 *s_loc = reinterpret_cast<int4 *>(lds + C::LOC_OFF);
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -567,9 +577,7 @@ __global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__re
     const int wgs = gridDim.x >> 3, xcd = blockIdx.x & 7, wg = blockIdx.x >> 3;
     int mine, first;
     {
-        TileScan<C::BT> sc;
-        sc.init(offsets, N);
-        const int items = sc.tiles * n_ftiles, per_xcd = (items + 7) / 8;
+        const int items = scan0.tiles * n_ftiles, per_xcd = (items + 7) / 8;
         const int lo = xcd * per_xcd, hi = min(lo + per_xcd, items);
         first = lo + wg;
         mine = first < hi ? (hi - first + wgs - 1) / wgs : 0;
@@ -580,7 +588,7 @@ __global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__re
         const int nq = min(C::MAXQ, mine - q0);
         if (q0 > 0) __syncthreads();  // everybody has left the tables and the ring of the batch before
         {
-            TileScan<C::BT> sc;
+            TileScan<C> sc;
             sc.init(offsets, N);
             for (int q = wave; q < nq; q += C::NW) {
                 const int4 loc = sc.locate(first + (q0 + q) * wgs, n_ftiles);
@@ -618,6 +626,46 @@ __global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__re
             TileDispatch<C, GATEUP, TILED, C::G>::run(st, (loc.z + 63) >> 6, loc.x, loc.y, loc.z, loc.w);
         }
     }
+}
+
+template <class C, bool GATEUP, bool TILED>
+__global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__restrict__ tok,
+                                                              const bf16_t *__restrict__ w0,
+                                                              const bf16_t *__restrict__ w1,
+                                                              const int32_t *__restrict__ offsets,
+                                                              const int32_t *__restrict__ sorted_slot,
+                                                              bf16_t *__restrict__ out, int N, int K, int Kdim, int Fdim,
+                                                              int n_ftiles, int T)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    TileScan<C> sc;
+    sc.init(offsets, N);
+    run_tiles<C, GATEUP, TILED>(lds, sc, tok, w0, w1, offsets, sorted_slot, out, N, K, Kdim, Fdim, n_ftiles, T);
+}
+
+// The same with two tile geometries in one kernel, chosen from the expert loads when the kernel starts: CB, whose
+// token tile is wider than 256 rows, where it makes noticeably fewer passes over expert weights than CA (experts
+// with a few rows more than CA's tile would otherwise stream their weights twice), else CA.  Every wave computes
+// the same choice from expert_offsets.
+template <class CA, class CB, bool GATEUP, bool TILED>
+__global__ __launch_bounds__(CA::THREADS) void ffn_bf16_adaptive_kernel(const bf16_t *__restrict__ tok,
+                                                                        const bf16_t *__restrict__ w0,
+                                                                        const bf16_t *__restrict__ w1,
+                                                                        const int32_t *__restrict__ offsets,
+                                                                        const int32_t *__restrict__ sorted_slot,
+                                                                        bf16_t *__restrict__ out, int N, int K, int Kdim,
+                                                                        int Fdim, int n_ftiles, int T)
+{
+    static_assert(CA::THREADS == CB::THREADS && CA::BF == CB::BF, "one launch shape, one feature tiling");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    TileScan<CA> sa;
+    sa.init(offsets, N);
+    TileScan<CB> sb;
+    sb.init(sa.off);
+    if (sb.tiles * 16 <= sa.tiles * 15)  // at least one pass in sixteen saved
+        run_tiles<CB, GATEUP, TILED>(lds, sb, tok, w0, w1, offsets, sorted_slot, out, N, K, Kdim, Fdim, n_ftiles, T);
+    else
+        run_tiles<CA, GATEUP, TILED>(lds, sa, tok, w0, w1, offsets, sorted_slot, out, N, K, Kdim, Fdim, n_ftiles, T);
 }
 
 // Tiled weight layout.  A matrix W[F][Kd] (F, Kd multiples of 32) is stored as (F/32) x (Kd/32) units of 2 KiB,

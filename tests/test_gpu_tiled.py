@@ -117,3 +117,25 @@ def test_chunk_counts_around_the_ring_depth(H, I, tiled):
     L = harness.gapped_layer(w, "cuda")
     res, st = full_parity(w, L, tiled=tiled)
     assert st["R"] > 0 and np.isfinite(res["out"].float().numpy()).all()
+
+
+# Expert loads just above the 256-row token tile: the tiled path then launches the kernel that holds two tile
+# geometries and picks, on the device, the 320-row one when it saves passes over expert weights.  Cases: every
+# expert in (256, 320] (static layer), about half of them there (zero experts present), loads well above the window
+# (the kernel falls back to 256-row tiles), and loads spread on both sides of it.
+ADAPTIVE_CASES = [
+    dict(T=2300, H=256, I=128, N=8, Z=0, K=1, seed=91, zero_bias=0.0),
+    dict(T=1150, H=256, I=128, N=8, Z=4, K=4, seed=92, zero_bias=0.45),
+    dict(T=1700, H=256, I=256, N=8, Z=4, K=4, seed=93, zero_bias=0.2),
+    dict(T=1150, H=512, I=128, N=6, Z=6, K=3, seed=94, zero_bias=0.1),
+]
+
+
+@pytest.mark.parametrize("cfg", ADAPTIVE_CASES, ids=lambda c: "T%d_H%d_I%d_N%d_Z%d_K%d" % (c["T"], c["H"], c["I"], c["N"], c["Z"], c["K"]))
+def test_loads_around_the_wide_token_tile(cfg):
+    w = synth.Workload("adaptive", dtype="bf16", recipe="zero_bias", x_std=1.0, w_std=0.05, wr_std=0.05, **cfg)
+    L = harness.gapped_layer(w, "cuda")
+    res, st = full_parity(w, L, tiled=True)
+    rows = np.diff(res["expert_offsets"].numpy())
+    _say("adaptive", w, "rows per expert", rows.tolist())
+    assert st["R"] > 0
