@@ -17,21 +17,27 @@ def _say(*a):
     print(*a, flush=True)
 
 
-def test_config3_decode_full():
+# bench.py times the tiled weight layout; the row-major layout is the other one the library accepts
+LAYOUTS = pytest.mark.parametrize("tiled", [True, False], ids=["tiled", "row_major"])
+
+
+@LAYOUTS
+def test_config3_decode_full(tiled):
     w = synth.CONFIGS["c3_qwen_decode"]
-    _say("config 3", w)
+    _say("config 3", w, "tiled" if tiled else "row-major")
     L = harness.gapped_layer(w, "cuda")
-    res, st = full_parity(w, L)
+    res, st = full_parity(w, L, tiled=tiled)
     _say(st)
     assert 0.35 < st["r_ze"] < 0.65 and st["nonempty"] < w.N
 
 
-def test_config2_prefill_full():
+@LAYOUTS
+def test_config2_prefill_full(tiled):
     w = synth.CONFIGS["c2_qwen_prefill"]
-    _say("config 2", w)
+    _say("config 2", w, "tiled" if tiled else "row-major")
     L = harness.gapped_layer(w, "cuda")
     _say("redrawn tokens:", L["redrawn"])
-    res, st = full_parity(w, L)
+    res, st = full_parity(w, L, tiled=tiled)
     _say(st)
     assert abs(st["r_ze"] - 0.5) < 0.02 and st["nonempty"] == w.N
 
@@ -46,13 +52,27 @@ def test_config2_static_layer_z0():
     assert st["R"] == w.T * w.K
 
 
-def test_config4_hetero_prefill_sampled():
+def test_config2_static_layer_z0_full_size_tiled():
+    # the same at T=4096 in the layout bench.py times: the experts average exactly 256 rows, half of them a few more,
+    # which is where the GEMM kernel switches to its 320-row token tile
+    w = synth.CONFIGS["c2_qwen_prefill"].with_(Z=0, recipe="plain")
+    _say("config 2 at Z=0, full size, tiled", w)
+    L = harness.gapped_layer(w, "cuda")
+    tokens = np.sort(np.random.default_rng(1).choice(w.T, size=256, replace=False))
+    res, st = full_parity(w, L, tokens=tokens, tiled=True)
+    load = np.diff(res["expert_offsets"].numpy())
+    _say(st, "rows per expert: min", load.min(), "max", load.max(), "above 256:", int((load > 256).sum()))
+    assert st["R"] == w.T * w.K and (load > 256).sum() > w.N // 4 and load.max() <= 320
+
+
+@LAYOUTS
+def test_config4_hetero_prefill_sampled(tiled):
     w = synth.CONFIGS["c4_hetero_prefill"]
-    _say("config 4", w)
+    _say("config 4", w, "tiled" if tiled else "row-major")
     L = harness.gapped_layer(w, "cuda")
     _say("redrawn tokens:", L["redrawn"])
     tokens = np.sort(np.random.default_rng(0).choice(w.T, size=192, replace=False))
-    res, st = full_parity(w, L, tokens=tokens)
+    res, st = full_parity(w, L, tokens=tokens, tiled=tiled)
     _say(st)
     zc = (res["topk_ids"].numpy() >= w.N).sum(axis=1)
     hist = np.bincount(zc, minlength=9) / w.T
