@@ -93,8 +93,8 @@ typedef TileCfg<1, 2, 2, 4, 4, 32> CfgDecode;   // 64 tokens x 128 weight rows, 
 // tiled weights come in 32-wide k blocks: 32-wide chunks, four deep
 typedef TileCfg<4, 2, 4, 4, 4, 32> CfgPrefillT;
 typedef TileCfg<4, 2, 2, 4, 4, 32> CfgNarrowT;
-// 320 tokens x 256 weight rows (token ring three deep): an expert with up to 320 rows is one token tile, so the
-// experts that CfgPrefillT would give a second, nearly empty tile stream their weights once.  It is the second
+// 320 tokens x 256 weight rows (token ring three deep): an expert with a few rows more than a multiple of 256 gets
+// one token tile less than CfgPrefillT would give it, i.e. one pass less over its weights.  It is the second
 // geometry of the adaptive kernel, which picks one of the two from the expert loads.
 typedef TileCfg<5, 2, 4, 4, 3, 32> CfgPrefillT5;
 
@@ -142,13 +142,18 @@ static int launch_adaptive_kernel(const zeda_layer_desc *d, const void *tok, con
     return last_launch_status();
 }
 
-// Whether the expert loads may sit just above the 256-row tile (the adaptive kernel then decides on the device; where
-// they cannot, the plain kernel saves the 1-2 % the second geometry costs the first).  The mean row count is T*K/N
-// when every slot is real and anything below that with zero experts.
+// Whether the expert loads may sit just above a multiple of the 256-row tile, where the wide tile saves a pass over
+// the weights (the adaptive kernel then decides on the device; where they cannot, the plain kernel saves the 1-2 %
+// the second geometry costs the first).  The mean row count is T*K/N when every slot is real - loads then cluster
+// around it - and anything below that with zero experts.
 static bool rows_may_straddle_tile(const zeda_layer_desc *d)
 {
     const double all_real = (double)d->T * d->K / d->N;
-    return d->Z == 0 ? (all_real > 240.0 && all_real <= 330.0) : (all_real > 256.0 && all_real < 1024.0);
+    // (at a thousand rows per expert and more the passes saved no longer pay for it: measured on config 4)
+    if (d->Z > 0) return all_real > 256.0 && all_real < 1024.0;
+    for (int k = 1; k <= 2; ++k)
+        if (all_real > 240.0 * k && all_real <= 330.0 * k) return true;
+    return false;
 }
 
 template <class C, bool GATEUP, bool TILED>

@@ -58,10 +58,15 @@ struct TileCfg {
     static constexpr int nlt(int g) { return 64 * g / RPI / NWT; }  // ... of a token wave with g live 64-row groups
     static constexpr int NLMAX = NLW > nlt(G) ? NLW : nlt(G);
     static constexpr int MAXQ = 8;                // items looked up at a time
-    // Token tiles of an expert with m rows: one tile while they fit, else tiles of at most 256 rows (a tile wider
-    // than 256 rows only pays where it saves a second pass over the expert's weights).
+    // Token tiles of an expert with m rows.  Tiles hold at most 256 rows unless the wider tile (BT > 256) saves a
+    // pass over the expert's weights (just above a multiple of 256 rows), and not for experts so large that the
+    // passes do not matter.
     static constexpr int SPLIT = BT < 256 ? BT : 256;
-    static __host__ __device__ constexpr int tiles_of(int m) { return m <= BT ? (m > 0 ? 1 : 0) : (m + SPLIT - 1) / SPLIT; }
+    static __host__ __device__ constexpr int tiles_of(int m)
+    {
+        const int narrow = (m + SPLIT - 1) / SPLIT, wide = (m + BT - 1) / BT;
+        return (wide < narrow && m <= 4 * BT) ? wide : narrow;
+    }
     static constexpr int TRING_OFF = WRING;
     static constexpr int TOK_OFF = WRING + TRING;            // int32 [MAXQ][BT]: source row of every tile row
     static constexpr int LOC_OFF = TOK_OFF + MAXQ * BT * 4;  // int4  [MAXQ]: expert, row0, rows, feature tile
