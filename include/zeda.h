@@ -110,8 +110,8 @@ int zeda_route(const zeda_layer_desc *desc, const void *x, const void *w_router,
  *   expert_offsets[e] = first row of expert e, expert_offsets[N] = R = number of real slots;
  *   sorted_slot[r] = s for r < R (entries past R are left untouched);
  *   slot_to_row[s] = r, or -1 for a zero-expert slot;  num_real[0] = R  (r_ZE = 1 - R/(T*K)).
- * ws: zeda_dispatch_workspace_bytes(desc) bytes; the sort needs no scratch today, the argument is part of the
- * interface so that it can. */
+ * ws: zeda_dispatch_workspace_bytes(desc) bytes of scratch (per-segment counts for long slot lists; short lists
+ * use none of it, the pointer must be valid all the same). */
 int zeda_dispatch(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t *expert_offsets /*[N+1]*/,
                   int32_t *sorted_slot /*[T*K]*/, int32_t *slot_to_row /*[T*K]*/, int32_t *num_real /*[1]*/,
                   void *ws, size_t ws_bytes, void *stream);

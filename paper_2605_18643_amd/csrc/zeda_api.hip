@@ -24,11 +24,6 @@ int check_desc(const zeda_layer_desc *d)
     return ZEDA_OK;
 }
 
-static size_t dispatch_ws_bytes(const zeda_layer_desc *)
-{
-    return 256;  // the dispatch needs no scratch; the argument is kept in the ABI and must be a valid pointer
-}
-
 static size_t act_bytes(const zeda_layer_desc *d)
 {
     return align_up((size_t)d->T * d->K * d->I * elt_size(d), 256);
@@ -104,7 +99,7 @@ static int forward_impl(const zeda_layer_desc *desc, const void *x, const void *
     }
     if ((rc = launch_route(desc, x, w_router, router_bias, ids, gates, route_ws, s)) != ZEDA_OK) return rc;
     mark(1 + ZEDA_STAGE_ROUTE);
-    if ((rc = launch_dispatch(desc, ids, offsets, sorted_slot, slot_to_row, num_real, num_real_out, s)) != ZEDA_OK) return rc;
+    if ((rc = launch_dispatch(desc, ids, offsets, sorted_slot, slot_to_row, num_real, num_real_out, w + L.dispatch_ws, s)) != ZEDA_OK) return rc;
     mark(1 + ZEDA_STAGE_DISPATCH);
     if ((rc = launch_gateup(desc, x, w_gate, w_up, offsets, sorted_slot, act, s)) != ZEDA_OK) return rc;
     mark(1 + ZEDA_STAGE_GATEUP);
@@ -196,7 +191,7 @@ int zeda_dispatch(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t 
         !aligned16(ws) || (reinterpret_cast<uintptr_t>(num_real) & 3u))
         return ZEDA_EINVAL;
     if (ws_bytes < dispatch_ws_bytes(desc)) return ZEDA_EWORKSPACE;
-    return launch_dispatch(desc, topk_ids, expert_offsets, sorted_slot, slot_to_row, num_real, nullptr,
+    return launch_dispatch(desc, topk_ids, expert_offsets, sorted_slot, slot_to_row, num_real, nullptr, ws,
                            (hipStream_t)stream);
 }
 

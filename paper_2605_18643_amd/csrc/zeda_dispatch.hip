@@ -7,6 +7,14 @@
 // the expert's first row (so no histogram and no scan across workgroups is needed, and workgroup e
 // publishes expert_offsets[e] itself).  A second pass writes each match at first row + matches before it.
 // Slots on zero experts get slot_to_row = -1 from the workgroup whose index their 256-slot group maps to.
+//
+// That kernel reads the whole slot list once per expert.  From about fifty thousand slots on a second form takes
+// over, linear in the number of slots: the list is cut into segments of 2048 slots; a first kernel counts, per
+// segment, the slots on every expert; a second one turns the counts into the first row of every (expert, segment)
+// pair and places the segment's slots.  Inside a 64-slot group a lane finds the lanes with the same expert from
+// eight ballots over the bits of the id (no loop over experts), its rank among them is a bit count, and the
+// running row of an expert lives in LDS per wave.  Still no atomics: in a group only the first lane of each expert
+// updates that expert's counter, and waves own disjoint counters, so the order is again ascending slot index.
 #include "zeda_internal.h"
 
 namespace zeda {
@@ -119,10 +127,160 @@ __global__ __launch_bounds__(kPlaceThreads) void dispatch_kernel(const int32_t *
     }
 }
 
-int launch_dispatch(const zeda_layer_desc *d, const int32_t *ids, int32_t *offsets, int32_t *sorted_slot,
-                    int32_t *slot_to_row, int32_t *num_real, int32_t *num_real_copy, hipStream_t s)
+// ---------------------------------------------------------------------------------------------
+// segmented form
+// ---------------------------------------------------------------------------------------------
+constexpr int kSegThreads = 512;
+constexpr int kSegWaves = kSegThreads / 64;
+constexpr int kSegGroups = 4;                                  // 64-slot groups per wave
+constexpr int kSegSlots = kSegWaves * kSegGroups * 64;         // 2048
+constexpr int kSegMax = 256;                                   // segments at most (the place kernel walks them all)
+constexpr int kSegMinSlots = 49152;                            // below this the one-kernel form is faster
+
+// lanes of the wave whose slot is on the same normal expert as this lane's (0 for a lane that is on none)
+__device__ __forceinline__ unsigned long long same_expert_lanes(int id, bool real)
 {
-    dispatch_kernel<<<d->N, kPlaceThreads, 0, s>>>(ids, d->T * d->K, d->N, offsets, sorted_slot, slot_to_row, num_real,
+    unsigned long long m = __ballot(real);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const unsigned long long bb = __ballot((id >> b) & 1);
+        m &= ((id >> b) & 1) ? bb : ~bb;
+    }
+    return real ? m : 0ull;
+}
+
+// s_cnt[wave][e] += number of this wave's slots on expert e, for its kSegGroups groups of 64 slots
+__device__ __forceinline__ void count_wave(const int32_t *__restrict__ ids, int S, int N, int first_slot, int *cnt_w)
+{
+    const int lane = threadIdx.x & 63;
+    for (int g = 0; g < kSegGroups; ++g) {
+        const int s = first_slot + g * 64 + lane;
+        const int id = s < S ? ids[s] : -1;
+        const bool real = (unsigned)id < (unsigned)N;
+        const unsigned long long m = same_expert_lanes(id, real);
+        // the first lane of every expert present adds the group's count (distinct experts, distinct addresses)
+        if (real && (m & ((1ull << lane) - 1ull)) == 0) cnt_w[id] += __popcll(m);
+    }
+}
+
+__global__ __launch_bounds__(kSegThreads) void dispatch_count_kernel(const int32_t *__restrict__ ids, int S, int N,
+                                                                     int32_t *__restrict__ hist /*[segments][N]*/)
+{
+    __shared__ int s_cnt[kSegWaves][kMaxExperts];
+    const int tid = threadIdx.x, wave = tid >> 6, seg = blockIdx.x;
+    for (int i = tid; i < kSegWaves * kMaxExperts; i += kSegThreads) (&s_cnt[0][0])[i] = 0;
+    __syncthreads();
+    count_wave(ids, S, N, seg * kSegSlots + wave * (kSegGroups * 64), s_cnt[wave]);
+    __syncthreads();
+    if (tid < N) {
+        int t = 0;
+#pragma unroll
+        for (int w = 0; w < kSegWaves; ++w) t += s_cnt[w][tid];
+        hist[(size_t)seg * N + tid] = t;
+    }
+}
+
+__global__ __launch_bounds__(kSegThreads) void dispatch_place_kernel(const int32_t *__restrict__ ids, int S, int N,
+                                                                     const int32_t *__restrict__ hist, int segments,
+                                                                     int32_t *__restrict__ expert_offsets,
+                                                                     int32_t *__restrict__ sorted_slot,
+                                                                     int32_t *__restrict__ slot_to_row,
+                                                                     int32_t *__restrict__ num_real,
+                                                                     int32_t *__restrict__ num_real_copy)
+{
+    __shared__ int s_cnt[kSegWaves][kMaxExperts];  // counts of this segment's waves, then their running rows
+    __shared__ int s_tot[kMaxExperts];             // rows of every expert in the whole list, then its first row
+    __shared__ int s_wsum[kMaxExperts / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, seg = blockIdx.x;
+    for (int i = tid; i < kSegWaves * kMaxExperts; i += kSegThreads) (&s_cnt[0][0])[i] = 0;
+    __syncthreads();
+    const int first_slot = seg * kSegSlots + wave * (kSegGroups * 64);
+    count_wave(ids, S, N, first_slot, s_cnt[wave]);
+
+    // thread e: rows of expert e in the segments before this one, and in all of them
+    int before = 0, total = 0;
+    if (tid < N) {
+#pragma unroll 8
+        for (int g = 0; g < segments; ++g) {  // (independent loads: several in flight)
+            const int c = hist[(size_t)g * N + tid];
+            total += c;
+            before += g < seg ? c : 0;
+        }
+    }
+    // exclusive scan of the totals over the experts (kMaxExperts = 4 waves of 64 values)
+    if (tid < kMaxExperts) {
+        int incl = tid < N ? total : 0;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(incl, o);
+            if (lane >= o) incl += v;
+        }
+        if (lane == 63) s_wsum[wave] = incl;
+        s_tot[tid] = incl - (tid < N ? total : 0);  // exclusive inside the wave
+    }
+    __syncthreads();  // (also: every wave's counts are in s_cnt)
+    if (tid < kMaxExperts) {
+        int add = 0;
+        for (int w = 0; w < wave; ++w) add += s_wsum[w];
+        const int first_row = s_tot[tid] + add;  // first row of expert tid
+        if (seg == 0 && tid < N) expert_offsets[tid] = first_row;
+        if (seg == 0 && tid == N - 1) {
+            const int R = first_row + total;
+            expert_offsets[N] = R;
+            num_real[0] = R;
+            if (num_real_copy) num_real_copy[0] = R;
+        }
+        // running row of (wave, expert): the expert's first row, the segments before, the waves before
+        int row = first_row + before;
+        if (tid < N) {
+#pragma unroll
+            for (int w = 0; w < kSegWaves; ++w) {
+                const int c = s_cnt[w][tid];
+                s_cnt[w][tid] = row;
+                row += c;
+            }
+        }
+    }
+    __syncthreads();
+
+    int *row_w = s_cnt[wave];
+    for (int g = 0; g < kSegGroups; ++g) {
+        const int s = first_slot + g * 64 + lane;
+        const int id = s < S ? ids[s] : -1;
+        const bool real = (unsigned)id < (unsigned)N;
+        const unsigned long long m = same_expert_lanes(id, real);
+        const int rank = __popcll(m & ((1ull << lane) - 1ull));
+        if (real) {
+            const int base = row_w[id];   // same value for all lanes of the expert: read before its first lane writes
+            const int r = base + rank;
+            sorted_slot[r] = s;
+            slot_to_row[s] = r;
+            if (rank == 0) row_w[id] = base + __popcll(m);
+        } else if (s < S) {
+            slot_to_row[s] = -1;
+        }
+    }
+}
+
+size_t dispatch_ws_bytes(const zeda_layer_desc *d)
+{
+    const size_t S = (size_t)d->T * d->K, segments = (S + kSegSlots - 1) / kSegSlots;
+    if (S < (size_t)kSegMinSlots || segments > (size_t)kSegMax) return 256;  // the one-kernel form needs no scratch
+    return align_up(segments * d->N * sizeof(int32_t), 256);
+}
+
+int launch_dispatch(const zeda_layer_desc *d, const int32_t *ids, int32_t *offsets, int32_t *sorted_slot,
+                    int32_t *slot_to_row, int32_t *num_real, int32_t *num_real_copy, void *ws, hipStream_t s)
+{
+    const int S = d->T * d->K, segments = (S + kSegSlots - 1) / kSegSlots;
+    if (S >= kSegMinSlots && segments <= kSegMax) {
+        int32_t *hist = (int32_t *)ws;
+        dispatch_count_kernel<<<segments, kSegThreads, 0, s>>>(ids, S, d->N, hist);
+        dispatch_place_kernel<<<segments, kSegThreads, 0, s>>>(ids, S, d->N, hist, segments, offsets, sorted_slot,
+                                                               slot_to_row, num_real, num_real_copy);
+        return last_launch_status();
+    }
+    dispatch_kernel<<<d->N, kPlaceThreads, 0, s>>>(ids, S, d->N, offsets, sorted_slot, slot_to_row, num_real,
                                                   num_real_copy);
     return last_launch_status();
 }

@@ -33,9 +33,10 @@ size_t route_ws_bytes(const zeda_layer_desc *d);
 int launch_routing_stats(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, float alpha, float w,
                          float *f, float *P, float *summary, void *ws, hipStream_t s);
 size_t routing_stats_ws_bytes(const zeda_layer_desc *d);
-// num_real_copy (may be NULL) receives num_real as well
+// num_real_copy (may be NULL) receives num_real as well; ws: dispatch_ws_bytes(d) of scratch
 int launch_dispatch(const zeda_layer_desc *d, const int32_t *ids, int32_t *offsets, int32_t *sorted_slot,
-                    int32_t *slot_to_row, int32_t *num_real, int32_t *num_real_copy, hipStream_t s);
+                    int32_t *slot_to_row, int32_t *num_real, int32_t *num_real_copy, void *ws, hipStream_t s);
+size_t dispatch_ws_bytes(const zeda_layer_desc *d);
 int launch_gateup(const zeda_layer_desc *d, const void *x, const void *wg, const void *wu, const int32_t *offsets,
                   const int32_t *sorted_slot, void *act, hipStream_t s);
 int launch_down(const zeda_layer_desc *d, const void *act, const void *wd, const int32_t *offsets, void *y_slot,

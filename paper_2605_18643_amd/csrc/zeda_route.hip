@@ -152,8 +152,14 @@ __device__ __forceinline__ void select_block(const float *lg, int LD, int pstrid
 // chunk, so each holds a partial sum over a quarter of the hidden dimension; each stores it in an LDS table
 // of its own and the selection adds the four tables in wave order (a fixed order: the logits are
 // reproducible); each wave selects for 8 tokens, four at a time (one per row of 16 lanes).
+// With many tokens the router rows, which every workgroup reads in full, are most of the traffic (640 KiB per
+// workgroup from L2 against 128 KiB of token rows): TB = 2 gives a workgroup two token blocks (64 tokens), which
+// halves that traffic per token; it is used once there are enough token blocks to fill the device without it.
 // ring depth: as many slots as fit in LDS, at most six
-constexpr int route_stages(int nb) { return 160 * 1024 / ((kRouteTokens + 32 * nb) * 128) < 6 ? 160 * 1024 / ((kRouteTokens + 32 * nb) * 128) : 6; }
+constexpr int route_stages(int nb, int tb = 1)
+{
+    return 160 * 1024 / ((32 * tb + 32 * nb) * 128) < 6 ? 160 * 1024 / ((32 * tb + 32 * nb) * 128) : 6;
+}
 
 __device__ __forceinline__ int route_swz(int row, int piece) { return piece ^ ((row >> 1) & 7); }
 
@@ -163,7 +169,7 @@ __device__ __forceinline__ void route_wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int NB>
+template <int NB, int TB>
 __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t *__restrict__ x,
                                                                    const bf16_t *__restrict__ wr,
                                                                    const float *__restrict__ bias, int T, int H, int N,
@@ -171,26 +177,27 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
                                                                    int32_t *__restrict__ ids, float *__restrict__ gates,
                                                                    float *__restrict__ partial, int Tpad)
 {
+    constexpr int TOK = 32 * TB;                  // tokens of the workgroup
     constexpr int LD = NB * 32 + 1;
-    constexpr int ROWS = kRouteTokens + 32 * NB;  // rows of one ring slot: tokens first, then router rows
+    constexpr int ROWS = TOK + 32 * NB;           // rows of one ring slot: tokens first, then router rows
     constexpr int STAGE = ROWS * 128;
-    constexpr int NL = 1 + NB;                    // wave load instructions (8 rows each) per chunk and wave
-    constexpr int kRouteStages = route_stages(NB);
-    static_assert(kRouteTokens == 32 && kRouteThreads == 256, "one token block, four waves");
-    static_assert(4 * kRouteTokens * LD * 4 <= kRouteStages * STAGE, "the four partial logit tables reuse the ring");
+    constexpr int NL = TB + NB;                   // wave load instructions (8 rows each) per chunk and wave
+    constexpr int kRouteStages = route_stages(NB, TB);
+    constexpr int NT = 4 / TB;                    // partial logit tables in LDS (the four waves' sums meet in them)
+    static_assert(kRouteTokens == 32 && kRouteThreads == 256 && (TB == 1 || TB == 2), "token blocks of 32, four waves");
+    static_assert(NT * TOK * LD * 4 <= kRouteStages * STAGE, "the partial logit tables reuse the ring");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     float *lg = reinterpret_cast<float *>(lds);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int t0 = blockIdx.x * kRouteTokens;
+    const int t0 = blockIdx.x * TOK;
     const int col = lane & 31, half = lane >> 5;
 
     const bf16_t *src[NL];
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
         const int row = (wave + 4 * i) * 8 + (lane >> 3), piece = lane & 7;
-        const bf16_t *base = row < kRouteTokens ? x + (size_t)min(t0 + row, T - 1) * H
-                                                : wr + (size_t)min(row - kRouteTokens, NE - 1) * H;
+        const bf16_t *base = row < TOK ? x + (size_t)min(t0 + row, T - 1) * H : wr + (size_t)min(row - TOK, NE - 1) * H;
         src[i] = base + route_swz(row, piece) * 8;
     }
     // All workgroups read the same router rows, and rows are a power-of-two number of bytes apart, so one
@@ -210,11 +217,13 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
                                              (__attribute__((address_space(3))) void *)(slot + (wave + 4 * i) * 1024), 16, 0, 0);
     };
 
-    f32x16 acc[NB];
+    f32x16 acc[NB][TB];
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+        for (int u = 0; u < TB; ++u)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[b][u][v] = 0.f;
 
 #pragma unroll
     for (int c = 0; c < kRouteStages - 1; ++c)
@@ -226,35 +235,53 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
         if (it + kRouteStages - 1 < nk) issue(it + kRouteStages - 1);
         const unsigned char *cur = lds + (it % kRouteStages) * STAGE;
         // this wave's 16-wide step of the chunk: pieces 2*wave and 2*wave+1 of every row
-        const bf16x8 tb = *reinterpret_cast<const bf16x8 *>(cur + col * 128 + route_swz(col, 2 * wave + half) * 16);
+        bf16x8 tb[TB];
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+            const int trow = u * 32 + col;
+            tb[u] = *reinterpret_cast<const bf16x8 *>(cur + trow * 128 + route_swz(trow, 2 * wave + half) * 16);
+        }
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            const int row = kRouteTokens + b * 32 + col;
+            const int row = TOK + b * 32 + col;
             const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(cur + row * 128 + route_swz(row, 2 * wave + half) * 16);
-            acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, tb, acc[b], 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < TB; ++u) acc[b][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, tb[u], acc[b][u], 0, 0, 0);
         }
     }
     __syncthreads();  // everyone is done with the ring: its memory now holds the logits
 
-    // acc[b][v]: expert 32b + 8(v/4) + 4*half + v%4, token col.  Every wave stores its partial sums in a table
-    // of its own; the selection adds the four tables in wave order (a fixed order) when it reads them.
-    float *mine = lg + wave * (kRouteTokens * LD);
+    // acc[b][u][v]: expert 32b + 8(v/4) + 4*half + v%4, token 32u + col.  The waves' partial sums (each over a
+    // quarter of the hidden dimension) meet in NT tables: wave w uses table w % NT, the waves of a table take turns
+    // in wave order, the first one storing and the later ones adding; the selection adds the tables in order.
+    // Every order is fixed, so the logits are reproducible.
+    float *mine = lg + (wave % NT) * (TOK * LD);
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int turn = 0; turn < 4 / NT; ++turn) {
+        if (wave / NT == turn) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mine[col * LD + b * 32 + 8 * (v >> 2) + 4 * half + (v & 3)] = acc[b][v];
-    __syncthreads();
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int u = 0; u < TB; ++u)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        float *p = mine + (u * 32 + col) * LD + b * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                        *p = turn == 0 ? acc[b][u][v] : *p + acc[b][u][v];
+                    }
+        }
+        __syncthreads();
+    }
     if (partial == nullptr) {
-        select_block<2 * NB, 4, 4>(lg, LD, kRouteTokens * LD, 4, bias, kRouteTokens, t0, T, NE, N, K, gate_norm, ids, gates);
+        select_block<2 * NB, NT, 4>(lg, LD, TOK * LD, NT, bias, TOK, t0, T, NE, N, K, gate_norm, ids, gates);
     } else {
-        // split-k launch: this workgroup's sums over its slice (the four wave tables added in wave order) go to
+        // split-k launch: this workgroup's sums over its slice (the tables added in order) go to
         // partial[blockIdx.y][token][expert]; route_select_kernel adds the slices in order and selects
         float *dst = partial + ((size_t)blockIdx.y * Tpad + t0) * (NB * 32);
-        for (int i = tid; i < kRouteTokens * NB * 32; i += kRouteThreads) {
+        for (int i = tid; i < TOK * NB * 32; i += kRouteThreads) {
             const int tk = i / (NB * 32), e = i - tk * (NB * 32);
             float v = lg[tk * LD + e];
 #pragma unroll
-            for (int q = 1; q < 4; ++q) v += lg[q * kRouteTokens * LD + tk * LD + e];
+            for (int q = 1; q < NT; ++q) v += lg[q * TOK * LD + tk * LD + e];
             dst[i] = v;
         }
     }
@@ -346,19 +373,41 @@ size_t route_ws_bytes(const zeda_layer_desc *d)
     return (size_t)c * Tpad * ceil_div(d->N + d->Z, 32) * 32 * sizeof(float);
 }
 
+// One kernel, no scratch, 64 tokens per workgroup: for token counts that fill the device with such blocks.
+template <int NB>
+static void launch_route_bf16_wide(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias,
+                                   int32_t *ids, float *gates, hipStream_t s)
+{
+    const int blocks = ceil_div(d->T, 64);
+    constexpr int lds_bytes = route_stages(NB, 2) * (64 + 32 * NB) * 128;
+    static bool attr_set = false;  // per instantiation; idempotent, so a race between host threads is harmless
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void *)route_bf16_kernel<NB, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        attr_set = true;
+    }
+    route_bf16_kernel<NB, 2><<<dim3(blocks, 1), kRouteThreads, lds_bytes, s>>>(
+        (const bf16_t *)x, (const bf16_t *)wr, bias, d->T, d->H, d->N, d->N + d->Z, d->K, d->gate_norm, ids, gates, nullptr,
+        blocks * 64);
+}
+
+constexpr int kRouteWideTokens = 12288;  // from here on the 64-token blocks alone give every CU a workgroup or nearly
+
 template <int NB>
 static void launch_route_bf16(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
                               float *gates, float *partial, hipStream_t s, bool logits_only = false)
 {
+    if constexpr (NB <= 6) {
+        if (!logits_only && d->T >= kRouteWideTokens) return launch_route_bf16_wide<NB>(d, x, wr, bias, ids, gates, s);
+    }
     const int blocks = ceil_div(d->T, kRouteTokens), Tpad = blocks * kRouteTokens;
     const int c = partial ? route_ksplit(d) : 1;
     constexpr int lds_bytes = route_stages(NB) * (kRouteTokens + 32 * NB) * 128;
     static bool attr_set = false;  // per instantiation; idempotent, so a race between host threads is harmless
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)route_bf16_kernel<NB>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        (void)hipFuncSetAttribute((const void *)route_bf16_kernel<NB, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         attr_set = true;
     }
-    route_bf16_kernel<NB><<<dim3(blocks, c), kRouteThreads, lds_bytes, s>>>(
+    route_bf16_kernel<NB, 1><<<dim3(blocks, c), kRouteThreads, lds_bytes, s>>>(
         (const bf16_t *)x, (const bf16_t *)wr, bias, d->T, d->H, d->N, d->N + d->Z, d->K, d->gate_norm, ids, gates,
         (c > 1 || logits_only) ? partial : nullptr, Tpad);
     if (logits_only) return;

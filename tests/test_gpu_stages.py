@@ -66,6 +66,25 @@ def test_route_with_scratch_splits_the_hidden_dimension(T, H):
         np.testing.assert_allclose(gates.cpu().numpy().astype(np.float64), rg, rtol=2e-5, atol=1e-7)
 
 
+@pytest.mark.parametrize("T, N, Z", [(12288, 128, 32), (12301, 30, 10), (13000, 150, 42), (12500, 200, 56)])
+def test_route_of_many_tokens(T, N, Z):
+    # from 12288 tokens on the bf16 router gives a workgroup 64 tokens instead of 32 (routers of up to 192
+    # experts; wider ones keep the 32-token blocks): exact ids and gates against the oracle, ragged last block
+    w = synth.Workload("route_wide", T=T, H=256, I=64, N=N, Z=Z, K=6, dtype="bf16", seed=53, recipe="zero_bias",
+                       wr_std=0.08, zero_bias=0.3)
+    print(w, flush=True)
+    L = harness.gapped_layer(w, "cuda")
+    d = desc_of(w)
+    ids = torch.full((w.T, w.K), -1, dtype=torch.int32, device="cuda")
+    gates = torch.full((w.T, w.K), float("nan"), dtype=torch.float32, device="cuda")
+    zeda.zeda_route(d, L["x"], L["w_router"], L["router_bias"], ids, gates)
+    torch.cuda.synchronize()
+    a = harness.to_arrays(L)
+    rid, rg = orc.route(a["x"], a["w_router"], a["router_bias"], w.N, w.Z, w.K)
+    assert np.array_equal(ids.cpu().numpy(), rid)
+    np.testing.assert_allclose(gates.cpu().numpy().astype(np.float64), rg, rtol=2e-5, atol=1e-7)
+
+
 def _dispatch(ids_np, N, Z, K):
     T = ids_np.shape[0]
     d = zeda.make_desc(T, 128, 64, N, Z, K, "bf16")
@@ -166,3 +185,32 @@ def test_combine_alone(dtype):
     else:
         check_float(w, got, ref, "out")
     assert not got[7].any()
+
+
+@pytest.mark.parametrize("T, N, Z, K", [(6144, 128, 32, 8), (7000, 5, 3, 7), (16384, 128, 32, 8), (65536, 256, 0, 8), (50000, 1, 3, 1)])
+def test_dispatch_of_long_slot_lists(T, N, Z, K):
+    # from about fifty thousand slots on the dispatch runs in its segmented form (two kernels, per-segment counts
+    # in the workspace): random ids, ragged last segment, one expert only, the widest router, and the sizes of the
+    # 8k and 16k-token benchmark configurations; everything is compared bit for bit with the oracle's counting sort
+    S = T * K
+    g = torch.Generator().manual_seed(T + N)
+    ids = torch.randint(0, N + Z, (T, K), generator=g, dtype=torch.int32)
+    if N > 2:
+        ids[ids == 1] = 0  # an empty expert in the middle of the list
+    d = zeda.make_desc(T, 128, 64, N, Z, K, "bf16")
+    need = zeda.dispatch_workspace_bytes(d)
+    assert need >= ((S + 2047) // 2048) * N * 4 if S >= 49152 else need > 0
+    dev = ids.cuda()
+    off = torch.full((N + 1,), -7, dtype=torch.int32, device="cuda")
+    ss = torch.full((S,), -7, dtype=torch.int32, device="cuda")
+    s2r = torch.full((S,), -7, dtype=torch.int32, device="cuda")
+    nreal = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    zeda.zeda_dispatch(d, dev, off, ss, s2r, nreal, ws)
+    torch.cuda.synchronize()
+    roff, rss, rs2r = orc.dispatch(ids.numpy(), N)
+    R = int(roff[N])
+    assert int(nreal.item()) == R
+    assert np.array_equal(off.cpu().numpy(), roff)
+    assert np.array_equal(ss.cpu().numpy()[:R], rss[:R]) and (ss.cpu().numpy()[R:] == -7).all()
+    assert np.array_equal(s2r.cpu().numpy(), rs2r.reshape(-1))
