@@ -206,7 +206,16 @@ def main() -> int:
                         "gateup_tflops": gu_flops / gu_s / 1e12, "down_tflops": dn_flops / dn_s / 1e12,
                         "down_gbs": dn_bytes / dn_s / 1e9},
         "stage_us": {k: v * 1e3 for k, v in stage.items()},
+        # algorithmic bytes of every stage over its event-timed duration
+        "stage_gbs": {
+            "route": (w.T * w.H * es + (w.N + w.Z) * w.H * es + w.T * w.K * 8) / (stage["route"] * 1e-3) / 1e9,
+            "dispatch": (w.T * w.K * 12 + w.N * 4) / (stage["dispatch"] * 1e-3) / 1e9,
+            "gateup": achieved_gbs,
+            "down": dn_bytes / dn_s / 1e9,
+            "combine": (R * w.H * es + w.T * w.H * es) / (stage["combine"] * 1e-3) / 1e9,
+        },
     }
+    res["config"]["mean_rows_per_expert"] = R / max(1, ne)
 
     if not a.no_z0 and w.Z > 0:
         # the same kernels on the static layer: no zero experts, top-K over the N normal experts only
