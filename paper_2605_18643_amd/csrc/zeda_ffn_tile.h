@@ -182,6 +182,16 @@ struct TileScan {
         }
         tiles = __shfl(incl, 63);
     }
+    // experts with at least one row (the same value in every lane)
+    __device__ __forceinline__ int experts() const
+    {
+        int ne = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) ne += nt[q] > 0;
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) ne += __shfl_xor(ne, o);
+        return ne;
+    }
     // (expert, first sorted row, rows, feature tile) of work item `item` = token tile * n_ftiles + feature tile;
     // the m rows of an expert are split evenly over its tiles, each a multiple of 64 rows except the last.
     __device__ __forceinline__ int4 locate(int item, int n_ftiles) const
@@ -206,7 +216,8 @@ struct TileScan {
     }
 };
 
-template <class C, bool GATEUP, bool TILED>
+// WNT: fetch the weights with the non-temporal hint (see run_tiles).
+template <class C, bool GATEUP, bool TILED, bool WNT = false>
 struct Stream {
     static constexpr int FB = C::FB, WF = C::WF, BT = C::BT, BF = C::BF, NSW = C::NSW, NST = C::NST, NW = C::NW,
                          NWW = C::NWW, NWT = C::NWT, WST = C::WST, TST = C::TST, KC = C::KC, KS = C::KS, ROWB = C::ROWB,
@@ -309,8 +320,13 @@ struct Stream {
     __device__ __forceinline__ void load_piece(int i)
     {
         const uint32_t dst = dbase + doff + i * ((NWW == NWT ? NWW : (wrole ? NWW : NWT)) * 1024);
-        __builtin_amdgcn_global_load_lds(ZEDA_GLOBAL_PTR(src[i] + koff),
-                                         (__attribute__((address_space(3))) void *)(uintptr_t)dst, 16, 0, 0);
+        // (the cache-policy field of the instruction is an immediate, hence two instructions)
+        if (WNT && wrole)
+            __builtin_amdgcn_global_load_lds(ZEDA_GLOBAL_PTR(src[i] + koff),
+                                             (__attribute__((address_space(3))) void *)(uintptr_t)dst, 16, 0, 2 /* nt */);
+        else
+            __builtin_amdgcn_global_load_lds(ZEDA_GLOBAL_PTR(src[i] + koff),
+                                             (__attribute__((address_space(3))) void *)(uintptr_t)dst, 16, 0, 0);
     }
     // the issue position moves on by one chunk inside the current item
     __device__ __forceinline__ void next_chunk_same_item()
@@ -549,24 +565,24 @@ struct Stream {
     }
 };
 
-template <class C, bool GATEUP, bool TILED, int GA>
+template <class S, int GA>
 struct TileDispatch {
-    static __device__ __forceinline__ void run(Stream<C, GATEUP, TILED> &st, int g, int expert, int row0, int rows, int ft)
+    static __device__ __forceinline__ void run(S &st, int g, int expert, int row0, int rows, int ft)
     {
         if (g == GA) st.template tile_body<GA>(expert, row0, rows, ft);
-        else TileDispatch<C, GATEUP, TILED, GA - 1>::run(st, g, expert, row0, rows, ft);
+        else TileDispatch<S, GA - 1>::run(st, g, expert, row0, rows, ft);
     }
 };
-template <class C, bool GATEUP, bool TILED>
-struct TileDispatch<C, GATEUP, TILED, 0> {
-    static __device__ __forceinline__ void run(Stream<C, GATEUP, TILED> &, int, int, int, int, int) {}
+template <class S>
+struct TileDispatch<S, 0> {
+    static __device__ __forceinline__ void run(S &, int, int, int, int, int) {}
 };
 
 // GATEUP: tok = x[T,Kdim], w0 = W_gate[N,Fdim,Kdim], w1 = W_up, out = act[S,Fdim] (Fdim = I, Kdim = H).
 // DOWN:   tok = act[S,Kdim], w0 = W_down[N,Fdim,Kdim], out = y_slot[S,Fdim]        (Fdim = H, Kdim = I).
 // Kdim is a multiple of KC; Fdim a multiple of the feature tile (BF/2 for GATEUP, BF for DOWN).
 // TILED: the weights are in the layout pack_weights_kernel writes.  The grid is a multiple of 8 workgroups.
-template <class C, bool GATEUP, bool TILED>
+template <class C, bool GATEUP, bool TILED, bool WNT>
 __device__ __forceinline__ void run_tiles(unsigned char *lds, const TileScan<C> &scan0, const bf16_t *__restrict__ tok,
                                           const bf16_t *__restrict__ w0,
                                           const bf16_t *__restrict__ w1, const int32_t *__restrict__ offsets,
@@ -609,7 +625,7 @@ __device__ __forceinline__ void run_tiles(unsigned char *lds, const TileScan<C> 
         }
         __syncthreads();
 
-        Stream<C, GATEUP, TILED> st;
+        Stream<C, GATEUP, TILED, WNT> st;
         st.tok = tok; st.w0 = w0; st.w1 = w1; st.out = out;
         st.Kdim = Kdim; st.Fdim = Fdim; st.nk = Kdim / C::KC;
         st.wring = lds; st.tring = lds + C::TRING_OFF; st.stg = lds + C::STG_OFF + wave * 2048; st.s_tok = s_tok; st.s_loc = s_loc;
@@ -628,9 +644,29 @@ __device__ __forceinline__ void run_tiles(unsigned char *lds, const TileScan<C> 
 
         for (int q = 0; q < nq; ++q) {
             const int4 loc = st.read_loc(q);
-            TileDispatch<C, GATEUP, TILED, C::G>::run(st, (loc.z + 63) >> 6, loc.x, loc.y, loc.z, loc.w);
+            TileDispatch<Stream<C, GATEUP, TILED, WNT>, C::G>::run(st, (loc.z + 63) >> 6, loc.x, loc.y, loc.z, loc.w);
         }
     }
+}
+
+// Weights that are read once - every expert one token tile - and that are what the kernel waits for - few rows per
+// expert - are fetched with the non-temporal hint: they then do not push the token rows, the activations and the
+// results, which this and the next kernels of the layer re-read, out of the caches (whole layer at 127 rows per
+// expert -4 %, at 3 rows -10 %; at 460 rows per expert the hint costs 2 % instead).  Decided once per launch from
+// the expert loads; the cache-policy field of the load is an immediate, so the two cases are two instantiations.
+template <class C, bool GATEUP, bool TILED>
+__device__ __forceinline__ void run_tiles_auto(unsigned char *lds, const TileScan<C> &scan0, const bf16_t *__restrict__ tok,
+                                               const bf16_t *__restrict__ w0, const bf16_t *__restrict__ w1,
+                                               const int32_t *__restrict__ offsets, const int32_t *__restrict__ sorted_slot,
+                                               bf16_t *__restrict__ out, int N, int K, int Kdim, int Fdim, int n_ftiles,
+                                               int T)
+{
+    const int ne = scan0.experts();
+    const bool stream_once = scan0.tiles * 16 <= ne * 17 && offsets[N] < 400 * ne;
+    if (stream_once)
+        run_tiles<C, GATEUP, TILED, true>(lds, scan0, tok, w0, w1, offsets, sorted_slot, out, N, K, Kdim, Fdim, n_ftiles, T);
+    else
+        run_tiles<C, GATEUP, TILED, false>(lds, scan0, tok, w0, w1, offsets, sorted_slot, out, N, K, Kdim, Fdim, n_ftiles, T);
 }
 
 template <class C, bool GATEUP, bool TILED>
@@ -645,7 +681,7 @@ __global__ __launch_bounds__(C::THREADS) void ffn_bf16_kernel(const bf16_t *__re
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     TileScan<C> sc;
     sc.init(offsets, N);
-    run_tiles<C, GATEUP, TILED>(lds, sc, tok, w0, w1, offsets, sorted_slot, out, N, K, Kdim, Fdim, n_ftiles, T);
+    run_tiles_auto<C, GATEUP, TILED>(lds, sc, tok, w0, w1, offsets, sorted_slot, out, N, K, Kdim, Fdim, n_ftiles, T);
 }
 
 // The same with two tile geometries in one kernel, chosen from the expert loads when the kernel starts: CB, whose
@@ -668,9 +704,9 @@ __global__ __launch_bounds__(CA::THREADS) void ffn_bf16_adaptive_kernel(const bf
     TileScan<CB> sb;
     sb.init(sa.off);
     if (sb.tiles * 16 <= sa.tiles * 15)  // at least one pass in sixteen saved
-        run_tiles<CB, GATEUP, TILED>(lds, sb, tok, w0, w1, offsets, sorted_slot, out, N, K, Kdim, Fdim, n_ftiles, T);
+        run_tiles_auto<CB, GATEUP, TILED>(lds, sb, tok, w0, w1, offsets, sorted_slot, out, N, K, Kdim, Fdim, n_ftiles, T);
     else
-        run_tiles<CA, GATEUP, TILED>(lds, sa, tok, w0, w1, offsets, sorted_slot, out, N, K, Kdim, Fdim, n_ftiles, T);
+        run_tiles_auto<CA, GATEUP, TILED>(lds, sa, tok, w0, w1, offsets, sorted_slot, out, N, K, Kdim, Fdim, n_ftiles, T);
 }
 
 // Tiled weight layout.  A matrix W[F][Kd] (F, Kd multiples of 32) is stored as (F/32) x (Kd/32) units of 2 KiB,
