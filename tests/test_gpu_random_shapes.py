@@ -1,14 +1,14 @@
 """GPU parity on seeded random layer shapes: whole-layer forward through the C ABI against the CPU oracle, over a
-spread of token counts, widths, router sizes and top-K values inside the library's documented limits, alternating
-the two expert-weight layouts.  The fixed lists of the other parity tests pick their shapes by hand; this one is
-there for the combinations nobody thought of.  Expert weights are drawn with std 0.8/sqrt(H), so that outputs stay
+spread of token counts, widths, router sizes, top-K values and gate normalisations inside the library's documented
+limits, alternating the two expert-weight layouts.  The fixed lists of the other parity tests pick their shapes by
+hand; this one is there for the combinations nobody thought of.  Expert weights are drawn with std 0.8/sqrt(H), so that outputs stay
 O(1) at every width and the absolute bf16 tolerance means the same thing in every case."""
 import random
 
 import pytest
 
 from oracle import harness
-from paper_2605_18643_amd import synth
+from paper_2605_18643_amd import synth, zeda
 
 pytestmark = pytest.mark.gpu
 
@@ -38,8 +38,9 @@ def test_random_shapes_match_oracle(block):
         i = block * per_block + j
         cfg = draw_case(rng, i)
         tiled = bool(i & 1)
-        print("random shape", i, cfg, "tiled" if tiled else "row_major", flush=True)
+        gate_norm = rng.choice([zeda.GATE_TOPK_NORM, zeda.GATE_SOFTMAX, zeda.GATE_REAL_RENORM])
+        print("random shape", i, cfg, "tiled" if tiled else "row_major", "gate_norm", gate_norm, flush=True)
         w = synth.Workload("random", dtype="bf16", recipe="zero_bias", x_std=1.0, w_std=0.8 / cfg["H"] ** 0.5,
                            wr_std=0.05, **cfg)
-        L = harness.gapped_layer(w, "cuda")
-        full_parity(w, L, tiled=tiled)
+        L = harness.gapped_layer(w, "cuda", gate_norm=gate_norm)
+        full_parity(w, L, gate_norm, tiled=tiled)
