@@ -400,3 +400,42 @@ def test_zero_expert_row_initialisation():
     rows, mean, var = orc.init_zero_rows(wr, r.standard_normal((2000, H)).astype(np.float32))
     assert np.mean(rows) == pytest.approx(mean, abs=4 * math.sqrt(var / rows.size))
     assert np.var(rows) == pytest.approx(var, rel=0.03)
+
+
+# ----------------------------------------------------------------------------------------------
+# Pre-norm of the layer-stack workload (the paper's layer has no norm: Appendix D leaves norms and residuals out
+# of its model; the stack of benchmark configuration 5 chains layers as x <- x + MoE(RMSNorm(x)))
+# ----------------------------------------------------------------------------------------------
+def test_rmsnorm_hand_cases():
+    # x = (3, 4): mean of squares 12.5, so without eps the row is divided by sqrt(12.5)
+    out = orc.rmsnorm(np.array([[3.0, 4.0]]), None, 0.0)
+    np.testing.assert_allclose(out, np.array([[3.0, 4.0]]) / math.sqrt(12.5), rtol=1e-15)
+    assert out[0, 0] == pytest.approx(0.8485281374238570, rel=1e-14)  # 3 / sqrt(12.5), typed in
+    # a unit-RMS row is left alone; scaling the input by c > 0 changes nothing when eps = 0
+    np.testing.assert_allclose(orc.rmsnorm(np.array([[1.0, -1.0, 1.0, -1.0]]), None, 0.0), [[1.0, -1.0, 1.0, -1.0]], rtol=1e-15)
+    x = np.random.default_rng(3).standard_normal((5, 24))
+    np.testing.assert_allclose(orc.rmsnorm(37.5 * x, None, 0.0), orc.rmsnorm(x, None, 0.0), rtol=1e-13)
+    # the mean is over the H entries of the row (not a sum, not over rows): rows of different scale are
+    # normalised separately, and every output row has mean square 1
+    xs = x * np.array([1e-3, 1.0, 10.0, 1e3, 1e5])[:, None]
+    np.testing.assert_allclose(np.mean(orc.rmsnorm(xs, None, 0.0) ** 2, axis=1), np.ones(5), rtol=1e-13)
+
+
+def test_rmsnorm_written_out_definition_gamma_and_eps():
+    r = np.random.default_rng(17)
+    x = r.standard_normal((7, 48)) * 1.7
+    gamma = r.uniform(0.5, 1.5, 48)
+    eps = 0.37  # large on purpose: an eps outside the root, or added to the sum instead of the mean, shows
+    want = x / np.sqrt(np.mean(x * x, axis=1, keepdims=True) + eps) * gamma[None, :]
+    np.testing.assert_allclose(orc.rmsnorm(x, gamma, eps), want, rtol=1e-14)
+    # gamma scales each column and nothing else
+    np.testing.assert_allclose(orc.rmsnorm(x, gamma, eps), orc.rmsnorm(x, None, eps) * gamma[None, :], rtol=1e-15)
+    assert not np.allclose(orc.rmsnorm(x, None, eps), orc.rmsnorm(x, None, 0.0), rtol=1e-3)
+    # an all-zero row: eps alone is under the root, the result is exactly zero (no 0/0)
+    z = np.zeros((1, 16))
+    out = orc.rmsnorm(z, None, 1e-6)
+    assert np.all(out == 0.0) and not np.isnan(out).any()
+    # a row far smaller than sqrt(eps) is scaled by 1/sqrt(eps), not normalised to unit size
+    tiny = np.full((1, 16), 1e-9)
+    np.testing.assert_allclose(orc.rmsnorm(tiny, None, 1e-6), tiny / math.sqrt(1e-6 + 1e-18), rtol=1e-14)
+    np.testing.assert_allclose(orc.rmsnorm(tiny, None, 1e-6), tiny * 1e3, rtol=1e-9)
