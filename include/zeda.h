@@ -21,8 +21,17 @@
  *     Their element type is desc->dtype (fp32, or bf16 with fp32 accumulation).  Indices are int32,
  *     routing weights fp32.
  *   - Inputs are never written.  Outputs are fully overwritten.
- *   - Return value: ZEDA_OK, or a negative zeda_status; on error nothing has been enqueued.
+ *   - Return value: ZEDA_OK, or a negative zeda_status.  Arguments are checked before anything is enqueued, so
+ *     ZEDA_EINVAL, ZEDA_EUNSUPPORTED and ZEDA_EWORKSPACE mean that nothing ran.  ZEDA_EHIP reports a failed launch or
+ *     runtime query; in an entry point that enqueues several kernels the earlier ones may already be on the stream
+ *     (outputs are then undefined).
  *   - Calls that share a workspace or output buffer must be ordered by the caller (same stream).
+ *   - Process state: none that a caller can observe, but launch geometry (workgroups the device holds at once) and the
+ *     kernels' opt-in to more than 64 KiB of LDS are looked up on the first call of each kernel variant on each device
+ *     and cached per device ordinal (up to 64 devices) for the life of the process.  Those first calls make runtime
+ *     queries that are not allowed during stream capture: run every entry point once, eagerly, on the device and
+ *     shape class that will be captured before capturing it into a HIP graph.  The calling thread's current device
+ *     must be the one that owns the pointers and the stream.
  *
  * Shape limits (ZEDA_EUNSUPPORTED otherwise): 1 <= K <= min(N+Z, 16); N+Z <= 256;
  * T*K < 2^24; bf16: H % 128 == 0 and I % 64 == 0; fp32: H % 4 == 0, I % 4 == 0, H and I <= 12288.
@@ -135,7 +144,7 @@ int zeda_combine(const zeda_layer_desc *desc, const void *y_slot, const int32_t 
                  const int32_t *slot_to_row, const void *x, void *out /*[T,H]*/, void *stream);
 
 /* The whole layer: route -> dispatch -> expert FFN -> combine, all on `stream`.
- * num_real_out[0] (device, may be NULL) receives R.  ws: scratch of zeda_workspace_bytes(desc); after
+ * num_real_out[0] (device, may be NULL) receives R (0 when T = 0, which enqueues nothing else).  ws: scratch of zeda_workspace_bytes(desc); after
  * the call it holds the intermediate results at the offsets zeda_workspace_layout reports. */
 int zeda_moe_forward(const zeda_layer_desc *desc, const void *x, const void *w_router, const float *router_bias,
                      const void *w_gate, const void *w_up, const void *w_down, void *out /*[T,H]*/,

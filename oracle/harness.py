@@ -29,17 +29,18 @@ def topk_gaps(logits: np.ndarray, K: int) -> np.ndarray:
 
 
 def gapped_layer(w: synth.Workload, device="cpu", layer: int = 0, max_rounds: int = 64,
-                 gate_norm: int = orc.GATE_TOPK_NORM) -> Dict[str, object]:
+                 gate_norm: int = orc.GATE_TOPK_NORM, planted: Optional[np.ndarray] = None) -> Dict[str, object]:
     """Draw a layer whose routing is unambiguous: rows of x whose top K+1 fp32 logits (oracle, double
     accumulation, rounded once) have a neighbouring pair closer than GAP are re-drawn with the next
     attempt counter until none is left.  Returns the tensors of synth.make_layer plus `attempt`,
-    `redrawn` (number of tokens moved at least once)."""
+    `redrawn` (number of tokens moved at least once).  planted: explicit routing plan of the "planted" recipe
+    (see synth.draw_tokens)."""
     attempt = torch.zeros(w.T, dtype=torch.int64)
     wr_t, bias_t = synth.draw_router(w, "cpu", layer)
     wr = synth.to_numpy_f32(wr_t)
     bias = synth.to_numpy_f32(bias_t)
     for _ in range(max_rounds):
-        x = synth.to_numpy_f32(synth.draw_tokens(w, "cpu", attempt, layer))
+        x = synth.to_numpy_f32(synth.draw_tokens(w, "cpu", attempt, layer, planted))
         _, _, logits = orc.route(x, wr, bias, w.N, w.Z, w.K, gate_norm, want_logits=True)
         bad = topk_gaps(logits, w.K) < GAP
         if not bad.any():
@@ -47,7 +48,7 @@ def gapped_layer(w: synth.Workload, device="cpu", layer: int = 0, max_rounds: in
         attempt[torch.from_numpy(bad)] += 1
     else:
         raise RuntimeError("gap enforcement did not converge")
-    out = synth.make_layer(w, device, attempt, layer)
+    out = synth.make_layer(w, device, attempt, layer, planted)
     out["attempt"] = attempt
     out["redrawn"] = int((attempt > 0).sum())
     return out

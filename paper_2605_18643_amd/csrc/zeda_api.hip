@@ -47,6 +47,9 @@ static void layout_of(const zeda_layer_desc *d, zeda_ws_layout *L)
     L->total = o;
 }
 
+// one int32 written on the stream (a kernel rather than a memset node, so that captured graphs replay it reliably)
+__global__ void store_i32_kernel(int32_t *p, int32_t v) { *p = v; }
+
 // Tail of the pre-norm residual block variant: the combine adds into x_res and writes the next layer's input.
 struct BlockTail {
     void *x_res;
@@ -93,7 +96,11 @@ static int forward_impl(const zeda_layer_desc *desc, const void *x, const void *
         if (events && hipEventRecord((hipEvent_t)events[i], s) != hipSuccess) rc = ZEDA_EHIP;
     };
     mark(0);
-    if (desc->T == 0) {
+    if (desc->T == 0) {  // no token: nothing to route, R = 0
+        if (num_real_out) {
+            store_i32_kernel<<<1, 1, 0, s>>>(num_real_out, 0);
+            if (last_launch_status() != ZEDA_OK) return ZEDA_EHIP;
+        }
         for (int i = 1; i <= ZEDA_NUM_STAGES; ++i) mark(i);
         return rc;
     }

@@ -103,12 +103,14 @@ typedef TileCfg<5, 2, 4, 4, 3, 32> CfgPrefillT5;
 template <class C, bool GATEUP, bool TILED>
 static int resident_grid()
 {
-    static int grid = 0;  // per instantiation; idempotent, so a race between host threads is harmless
+    static int grids[kMaxDevices] = {};  // per instantiation and device; idempotent, so a race between host threads is harmless
+    const int dev = current_device();
+    if (dev < 0) return 0;
+    int &grid = grids[dev];
     if (grid == 0) {
         auto kern = ffn_bf16_kernel<C, GATEUP, TILED>;
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        int cus = 0, per_cu = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
             hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess ||
             hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kern, C::THREADS, C::LDS_BYTES) != hipSuccess)
             return 0;
@@ -124,11 +126,13 @@ static int launch_adaptive_kernel(const zeda_layer_desc *d, const void *tok, con
 {
     constexpr int kLds = CA::LDS_BYTES > CB::LDS_BYTES ? CA::LDS_BYTES : CB::LDS_BYTES;
     auto kern = ffn_bf16_adaptive_kernel<CA, CB, GATEUP, TILED>;
-    static int grid = 0;  // (as in resident_grid)
+    static int grids[kMaxDevices] = {};  // (as in resident_grid)
+    const int dev = current_device();
+    if (dev < 0) return ZEDA_EHIP;
+    int &grid = grids[dev];
     if (grid == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        int cus = 0, per_cu = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
             hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess ||
             hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kern, CA::THREADS, kLds) != hipSuccess)
             return ZEDA_EHIP;

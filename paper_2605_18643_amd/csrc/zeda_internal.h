@@ -17,7 +17,15 @@ constexpr int kWave = 64;
 constexpr int kMaxExperts = 256;  // N + Z
 constexpr int kMaxK = 16;
 
+constexpr int kMaxDevices = 64;   // launch geometry and kernel attributes are cached per device ordinal below this
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+// ordinal of the calling thread's current device, or -1 (no device, or an ordinal past kMaxDevices)
+inline int current_device()
+{
+    int dev = 0;
+    return (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) ? dev : -1;
+}
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 int check_desc(const zeda_layer_desc *d);  // ZEDA_OK / ZEDA_EINVAL / ZEDA_EUNSUPPORTED

@@ -374,27 +374,40 @@ size_t route_ws_bytes(const zeda_layer_desc *d)
 }
 
 // One kernel, no scratch, 64 tokens per workgroup: for token counts that fill the device with such blocks.
+// The router kernels use more LDS than a launch gets by default: opt in once per kernel and device.
+template <int NB, int TB>
+static bool route_lds_opt_in(int lds_bytes)
+{
+    static bool done[kMaxDevices] = {};  // per instantiation and device; idempotent, so a race between host threads is harmless
+    const int dev = current_device();
+    if (dev < 0) return false;
+    if (!done[dev]) {
+        if (hipFuncSetAttribute((const void *)route_bf16_kernel<NB, TB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                lds_bytes) != hipSuccess)
+            return false;
+        done[dev] = true;
+    }
+    return true;
+}
+
 template <int NB>
-static void launch_route_bf16_wide(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias,
-                                   int32_t *ids, float *gates, hipStream_t s)
+static int launch_route_bf16_wide(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias,
+                                  int32_t *ids, float *gates, hipStream_t s)
 {
     const int blocks = ceil_div(d->T, 64);
     constexpr int lds_bytes = route_stages(NB, 2) * (64 + 32 * NB) * 128;
-    static bool attr_set = false;  // per instantiation; idempotent, so a race between host threads is harmless
-    if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)route_bf16_kernel<NB, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        attr_set = true;
-    }
+    if (!route_lds_opt_in<NB, 2>(lds_bytes)) return ZEDA_EHIP;
     route_bf16_kernel<NB, 2><<<dim3(blocks, 1), kRouteThreads, lds_bytes, s>>>(
         (const bf16_t *)x, (const bf16_t *)wr, bias, d->T, d->H, d->N, d->N + d->Z, d->K, d->gate_norm, ids, gates, nullptr,
         blocks * 64);
+    return last_launch_status();
 }
 
 constexpr int kRouteWideTokens = 12288;  // from here on the 64-token blocks alone give every CU a workgroup or nearly
 
 template <int NB>
-static void launch_route_bf16(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
-                              float *gates, float *partial, hipStream_t s, bool logits_only = false)
+static int launch_route_bf16(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
+                             float *gates, float *partial, hipStream_t s, bool logits_only = false)
 {
     if constexpr (NB <= 6) {
         if (!logits_only && d->T >= kRouteWideTokens) return launch_route_bf16_wide<NB>(d, x, wr, bias, ids, gates, s);
@@ -402,15 +415,11 @@ static void launch_route_bf16(const zeda_layer_desc *d, const void *x, const voi
     const int blocks = ceil_div(d->T, kRouteTokens), Tpad = blocks * kRouteTokens;
     const int c = partial ? route_ksplit(d) : 1;
     constexpr int lds_bytes = route_stages(NB) * (kRouteTokens + 32 * NB) * 128;
-    static bool attr_set = false;  // per instantiation; idempotent, so a race between host threads is harmless
-    if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)route_bf16_kernel<NB, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        attr_set = true;
-    }
+    if (!route_lds_opt_in<NB, 1>(lds_bytes)) return ZEDA_EHIP;
     route_bf16_kernel<NB, 1><<<dim3(blocks, c), kRouteThreads, lds_bytes, s>>>(
         (const bf16_t *)x, (const bf16_t *)wr, bias, d->T, d->H, d->N, d->N + d->Z, d->K, d->gate_norm, ids, gates,
         (c > 1 || logits_only) ? partial : nullptr, Tpad);
-    if (logits_only) return;
+    if (logits_only) return last_launch_status();
     const dim3 sgrid(ceil_div(d->T, kSelectTokens));
     const int NE = d->N + d->Z;
     if (c == 2)
@@ -419,6 +428,7 @@ static void launch_route_bf16(const zeda_layer_desc *d, const void *x, const voi
         route_select_kernel<NB, 4><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates);
     else if (c == 8)
         route_select_kernel<NB, 8><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates);
+    return last_launch_status();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -572,16 +582,18 @@ int launch_routing_stats(const zeda_layer_desc *d, const void *x, const void *wr
     int nsplit = 1;
     if (d->dtype == ZEDA_BF16) {
         nsplit = route_ksplit(d);
+        int rc;
         switch (NB) {
-            case 1: launch_route_bf16<1>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 2: launch_route_bf16<2>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 3: launch_route_bf16<3>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 4: launch_route_bf16<4>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 5: launch_route_bf16<5>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 6: launch_route_bf16<6>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 7: launch_route_bf16<7>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            default: launch_route_bf16<8>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 1: rc = launch_route_bf16<1>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 2: rc = launch_route_bf16<2>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 3: rc = launch_route_bf16<3>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 4: rc = launch_route_bf16<4>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 5: rc = launch_route_bf16<5>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 6: rc = launch_route_bf16<6>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            case 7: rc = launch_route_bf16<7>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
+            default: rc = launch_route_bf16<8>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
         }
+        if (rc != ZEDA_OK) return rc;
     } else {
         route_f32_kernel<<<ceil_div(d->T, kRouteF32Tokens), kRouteThreads, 0, s>>>(
             (const float *)x, (const float *)wr, bias, d->T, d->H, d->N, NE, d->K, d->gate_norm, nullptr, nullptr, logits, LDg);
@@ -608,14 +620,14 @@ int launch_route(const zeda_layer_desc *d, const void *x, const void *wr, const 
     const int NE = d->N + d->Z;
     if (d->dtype == ZEDA_BF16) {
         switch (ceil_div(NE, 32)) {
-            case 1: launch_route_bf16<1>(d, x, wr, bias, ids, gates, partial, s); break;
-            case 2: launch_route_bf16<2>(d, x, wr, bias, ids, gates, partial, s); break;
-            case 3: launch_route_bf16<3>(d, x, wr, bias, ids, gates, partial, s); break;
-            case 4: launch_route_bf16<4>(d, x, wr, bias, ids, gates, partial, s); break;
-            case 5: launch_route_bf16<5>(d, x, wr, bias, ids, gates, partial, s); break;
-            case 6: launch_route_bf16<6>(d, x, wr, bias, ids, gates, partial, s); break;
-            case 7: launch_route_bf16<7>(d, x, wr, bias, ids, gates, partial, s); break;
-            default: launch_route_bf16<8>(d, x, wr, bias, ids, gates, partial, s); break;
+            case 1: return launch_route_bf16<1>(d, x, wr, bias, ids, gates, partial, s);
+            case 2: return launch_route_bf16<2>(d, x, wr, bias, ids, gates, partial, s);
+            case 3: return launch_route_bf16<3>(d, x, wr, bias, ids, gates, partial, s);
+            case 4: return launch_route_bf16<4>(d, x, wr, bias, ids, gates, partial, s);
+            case 5: return launch_route_bf16<5>(d, x, wr, bias, ids, gates, partial, s);
+            case 6: return launch_route_bf16<6>(d, x, wr, bias, ids, gates, partial, s);
+            case 7: return launch_route_bf16<7>(d, x, wr, bias, ids, gates, partial, s);
+            default: return launch_route_bf16<8>(d, x, wr, bias, ids, gates, partial, s);
         }
     } else {
         dim3 grid(ceil_div(d->T, kRouteF32Tokens));

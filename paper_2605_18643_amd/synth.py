@@ -285,9 +285,12 @@ def draw_router(w: Workload, device="cpu", layer: int = 0):
     return wr.to(w.torch_dtype), bias
 
 
-def draw_tokens(w: Workload, device="cpu", attempt: Optional[torch.Tensor] = None, layer: int = 0) -> torch.Tensor:
+def draw_tokens(w: Workload, device="cpu", attempt: Optional[torch.Tensor] = None, layer: int = 0,
+                planted: Optional[np.ndarray] = None) -> torch.Tensor:
     """x[T,H] in the workload's dtype.  `attempt[t]` (int64, default 0) re-draws row t; the caller
-    uses it to move tokens whose routing would be too close to a tie."""
+    uses it to move tokens whose routing would be too close to a tie.
+    planted ("planted" recipe only): a bool mask [T, N+Z] with K entries per row that replaces the seeded
+    routing plan (tests that need prescribed expert loads)."""
     seed = w.seed + layer
     dev = torch.device(device)
     kx = make_key(seed, TAG_X)
@@ -295,9 +298,10 @@ def draw_tokens(w: Workload, device="cpu", attempt: Optional[torch.Tensor] = Non
     if w.recipe == "planted":
         # Expert e owns hidden coordinate coord[e]; a token carries plant_x there for each expert
         # of its plan and exactly 0 on the coordinates of all other experts.
-        plan = planted_plan(w.with_(seed=seed))
+        if planted is None:
+            planted = planted_plan(w.with_(seed=seed))["planted"]
         coord_t = torch.from_numpy(_plant_coords(w, seed)).to(dev)
-        mask = torch.from_numpy(plan["planted"]).to(dev)
+        mask = torch.from_numpy(np.asarray(planted, dtype=bool)).to(dev)
         x[:, coord_t] = torch.where(mask, torch.tensor(w.plant_x, device=dev), torch.tensor(0.0, device=dev))
     return x.to(w.torch_dtype)
 
@@ -314,12 +318,12 @@ def draw_experts(w: Workload, device="cpu", layer: int = 0):
 
 
 def make_layer(w: Workload, device="cpu", attempt: Optional[torch.Tensor] = None,
-               layer: int = 0) -> Dict[str, Optional[torch.Tensor]]:
+               layer: int = 0, planted: Optional[np.ndarray] = None) -> Dict[str, Optional[torch.Tensor]]:
     """All tensors of one layer: x, w_router, router_bias, w_gate, w_up, w_down.
-    `layer` offsets the seed (stack workloads)."""
+    `layer` offsets the seed (stack workloads); `planted` as in draw_tokens."""
     wr, bias = draw_router(w, device, layer)
     wg, wu, wd = draw_experts(w, device, layer)
-    return {"x": draw_tokens(w, device, attempt, layer), "w_router": wr, "router_bias": bias,
+    return {"x": draw_tokens(w, device, attempt, layer, planted), "w_router": wr, "router_bias": bias,
             "w_gate": wg, "w_up": wu, "w_down": wd}
 
 

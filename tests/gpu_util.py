@@ -72,13 +72,16 @@ def check_float(w, got: np.ndarray, ref: np.ndarray, what: str):
 
 
 def full_parity(w: synth.Workload, L, gate_norm=zeda.GATE_TOPK_NORM, tokens=None, tiled=False, copy_expert=False):
-    """Whole-layer parity.  With `tokens` (sorted indices) the oracle's expert arithmetic runs on those
-    rows only; routing and dispatch are always checked on every token."""
+    """Whole-layer parity.  With `tokens` (sorted indices, or a function of the reference ids, offsets and
+    slot_to_row that returns them) the oracle's expert arithmetic runs on those rows only; routing and dispatch
+    are always checked on every token."""
     a = harness.to_arrays(L)
     res = forward(w, L, gate_norm, tiled, copy_expert)
     ref_ids, ref_gates = orc.route(a["x"], a["w_router"], a["router_bias"], w.N, w.Z, w.K, gate_norm)
     check_routing(w, res, ref_ids, ref_gates)
     off, ss, s2r, R = check_dispatch(w, res, ref_ids)
+    if callable(tokens):
+        tokens = tokens(ref_ids, off, s2r)
     ref = harness.oracle_forward(w, a, gate_norm, copy_expert=copy_expert, tokens=tokens, want_y_slot=True)
     tok = np.arange(w.T) if tokens is None else np.asarray(tokens)
     assert np.array_equal(ref["ids"], ref_ids[tok])

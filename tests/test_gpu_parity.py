@@ -119,3 +119,4 @@ def test_empty_batch_is_a_no_op_on_every_entry_point():
     torch.cuda.synchronize()
     assert (guard.float() == 7.0).all() and (ids == -9).all() and (gates == -9.0).all()
     assert not off.cpu().numpy().any() and int(nr.item()) == 0 and (ss == -5).all() and (s2r == -5).all()
+    assert int(nreal.item()) == 0  # the whole-layer call reports R = 0

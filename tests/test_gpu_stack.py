@@ -127,21 +127,24 @@ def test_tiny_fp32_stack_end_to_end(fused):
     else:
         out = st.forward(x.clone(), hook=lambda l, s: ids_gpu.append(zeda.ws_views(s.desc, s.ws)["topk_ids"].clone()))
     torch.cuda.synchronize()
-    excluded = 0
+    # A token whose routing is ambiguous in some layer may legitimately differ from then on; the chain is
+    # token by token (no layer mixes rows), so every other token must follow the oracle chain to the end.
+    ever_unsafe = np.zeros(w.T, dtype=bool)
     for l, p in enumerate(st.weights):
         xn = orc.rmsnorm(ref, None, EPS).astype(np.float32)
         a = {k: synth.to_numpy_f32(v) for k, v in p.items()}
         r = orc.moe_forward(xn, a["w_router"], a["router_bias"], a["w_gate"], a["w_up"], a["w_down"], w.N, w.Z, w.K)
         _, _, lg = orc.route(xn, a["w_router"], a["router_bias"], w.N, w.Z, w.K, want_logits=True)
-        safe = harness.topk_gaps(lg, w.K) >= harness.GAP
-        excluded += int((~safe).sum())
+        ever_unsafe |= harness.topk_gaps(lg, w.K) < harness.GAP
         if not fused:
-            assert np.array_equal(ids_gpu[l].cpu().numpy()[safe], r["ids"][safe])
+            assert np.array_equal(ids_gpu[l].cpu().numpy()[~ever_unsafe], r["ids"][~ever_unsafe]), f"layer {l}"
         ref = ref + r["out"]
-    _say("tokens excluded from the routing comparison over 4 layers:", excluded)
+    keep = ~ever_unsafe
+    _say("tokens left out of the comparison (near-tie in some layer):", int(ever_unsafe.sum()), "of", w.T)
+    assert keep.sum() >= w.T // 2
     got = out.double().cpu().numpy()
-    # a token whose routing is ambiguous may legitimately differ afterwards: compare the others
-    assert harness.rel_l2(got, ref) < 1e-3 or excluded > 0
+    assert harness.rel_l2(got[keep], ref[keep]) < 1e-5
+    assert np.max(np.abs(got[keep] - ref[keep])) <= 1e-5 * np.max(np.abs(ref[keep]))
     assert np.isfinite(got).all()
 
 
@@ -177,7 +180,7 @@ def test_config5_stack_teacher_forced():
         # dispatch is exact for the ids the GPU actually used
         roff, _, _ = orc.dispatch(ids_h, w.N)
         assert np.array_equal(off.cpu().numpy(), roff)
-        tok = np.sort(rng.choice(np.flatnonzero(safe), size=96, replace=False))
+        tok = np.sort(rng.choice(np.flatnonzero(safe), size=1024, replace=False))
         r = orc.moe_forward(xn_h[tok], a["w_router"], a["router_bias"], a["w_gate"], a["w_up"], a["w_down"], w.N, w.Z, w.K)
         rl2, mabs = check_float(w, y.float().cpu().numpy()[tok], r["out"], f"layer {l} output")
         _say(f"layer {l}: {int((~safe).sum())} of {w.T} tokens excluded from the routing comparison; "
@@ -220,7 +223,7 @@ def test_config5_fused_chain_teacher_forced():
         assert np.array_equal(ids_h[safe], rid[safe]), f"layer {l}"
         roff, _, _ = orc.dispatch(ids_h, w.N)
         assert np.array_equal(off.cpu().numpy(), roff)
-        tok = np.sort(rng.choice(np.flatnonzero(safe), size=96, replace=False))
+        tok = np.sort(rng.choice(np.flatnonzero(safe), size=1024, replace=False))
         r = orc.moe_forward(xn_h[tok], a["w_router"], a["router_bias"], *[synth.to_numpy_f32(v) for v in (wg, wu, wd)],
                             w.N, w.Z, w.K)
         want = x0.double().cpu().numpy()[tok] + r["out"]

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 
 from paper_2605_18643_amd import build as zbuild
 
-_spec = importlib.util.spec_from_file_location("lds_wait_check", os.path.join(zbuild.CSRC, "lds_wait_check.py"))
+_spec = importlib.util.spec_from_file_location("lds_wait_check", os.path.join(os.path.dirname(os.path.abspath(__file__)), "lds_wait_check.py"))
 lwc = importlib.util.module_from_spec(_spec)
 _spec.loader.exec_module(lwc)
 
