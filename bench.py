@@ -73,39 +73,112 @@ def run_layer(w: synth.Workload, L, steps: int, warmup: int):
             "max_rows": int(np.diff(off).max()), "out": out}
 
 
-def stack_bench(a) -> int:
-    """benchmark configuration 5: time the chained stack at Z=32 and at Z=0 (same weights, router restricted to the
+def time_stack(layers: int, steps: int, warmup: int, tiled: bool):
+    """benchmark configuration 5: the chained stack at Z=32 and at Z=0 (same expert weights, router restricted to the
     normal experts); one step = one pass of all layers over T=8192 tokens."""
     from paper_2605_18643_amd.stack import MoeStack
 
     w = synth.CONFIGS["c5_stack_layer"]
     res = {}
     x0 = synth.draw_tokens(w, "cuda")
-    for name, static in (("z32", False), ("z0", True)):
-        st = MoeStack(w, a.layers, static=static, tiled=(a.weights == "tiled"))
+    st = MoeStack(w, layers, tiled=tiled)
+    for name, stack in (("z32", st), ("z0", st.static_twin())):
         x = x0.clone()
-        for _ in range(max(1, a.warmup // 2)):
-            st.forward(x.copy_(x0))
+        for _ in range(max(1, warmup)):
+            stack.forward(x.copy_(x0))
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(a.steps):
-            st.forward(x.copy_(x0))
+        for _ in range(steps):
+            stack.forward(x.copy_(x0))
         torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / a.steps
-        res[name] = {"ms_per_pass": dt * 1e3, "real_slots": int(st.num_real.sum().item())}
-        del st
-        torch.cuda.empty_cache()
+        dt = (time.perf_counter() - t0) / steps
+        res[name] = {"ms_per_pass": dt * 1e3, "real_slots": int(stack.num_real.sum().item())}
+    del st
+    torch.cuda.empty_cache()
+    return w, {"layers": layers, "T": w.T, "steps": steps, "warmup": warmup,
+               "tokens_per_s": w.T / (res["z32"]["ms_per_pass"] * 1e-3),
+               "z32": res["z32"], "z0": res["z0"],
+               "stack_speedup_vs_z0": res["z0"]["ms_per_pass"] / res["z32"]["ms_per_pass"],
+               "expert_flop_reduction": 1.0 - res["z32"]["real_slots"] / max(1, res["z0"]["real_slots"])}
+
+
+def stack_bench(a) -> int:
+    w, r = time_stack(a.layers, a.steps, max(1, a.warmup // 2), a.weights == "tiled")
     out = {"metric": "48-layer MoE stack tokens/s (Qwen3-30B-A3B layer shape, T=8192, ~50% zero slots)",
-           "value": w.T / (res["z32"]["ms_per_pass"] * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
-           "warmup": a.warmup, "ms_per_step": res["z32"]["ms_per_pass"], "higher_is_better": True, "scaling": "weak",
+           "value": r["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
+           "warmup": a.warmup, "ms_per_step": r["z32"]["ms_per_pass"], "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
            "config": {"workload": "c5_stack", "layers": a.layers, "T": w.T, "H": w.H, "I": w.I, "N": w.N, "Z": w.Z, "K": w.K,
                       "weight_layout": a.weights},
-           "z32": res["z32"], "z0": res["z0"],
-           "stack_speedup_vs_z0": res["z0"]["ms_per_pass"] / res["z32"]["ms_per_pass"],
-           "expert_flop_reduction": 1.0 - res["z32"]["real_slots"] / max(1, res["z0"]["real_slots"])}
+           "z32": r["z32"], "z0": r["z0"],
+           "stack_speedup_vs_z0": r["stack_speedup_vs_z0"],
+           "expert_flop_reduction": r["expert_flop_reduction"]}
     print(json.dumps(out))
     return 0
+
+
+def pack_layer(w, L):
+    """The layer with its expert weights in the library's tiled layout (packed once, as when a model is loaded)."""
+    L = dict(L)
+    L["w_gate"], L["w_up"], L["w_down"] = zeda.zeda_pack_expert_weights(
+        zeda.make_desc(w.T, w.H, w.I, w.N, w.Z, w.K, w.dtype), L["w_gate"], L["w_up"], L["w_down"])
+    L["weight_layout"] = zeda.WEIGHTS_TILED
+    return L
+
+
+def static_twin(w, L):
+    """The same layer without zero experts: top-K over the N normal experts only, same weights."""
+    L0 = dict(L)
+    L0["w_router"] = L["w_router"][: w.N].contiguous()
+    L0["router_bias"] = None
+    return w.with_(Z=0, recipe="plain"), L0
+
+
+def other_config_legs(tiled: bool):
+    """Short legs of benchmark configurations 3, 4 and 5 in the same run as the headline (each with its own
+    warm-up; times are HIP-event stage times and wall time per step as for the headline)."""
+    legs = {}
+    # configuration 3: decode shape, bound by streaming the weights of the experts that were hit
+    w = synth.CONFIGS["c3_qwen_decode"]
+    L = synth.make_layer(w, "cuda")
+    L = pack_layer(w, L) if tiled else L
+    r = run_layer(w, L, steps=400, warmup=200)
+    w0, L0 = static_twin(w, L)
+    r0 = run_layer(w0, L0, steps=400, warmup=100)
+    wbytes = 3.0 * w.H * w.I * 2 * r["nonempty"]
+    gu_s, dn_s = r["stage_ms"][2] * 1e-3, r["stage_ms"][3] * 1e-3
+    legs["c3_qwen_decode"] = {
+        "T": w.T, "ms_per_step": r["wall_s"] / 400 * 1e3, "tokens_per_s": w.T * 400 / r["wall_s"],
+        "real_slots": r["R"], "nonempty_experts": r["nonempty"], "expert_weight_bytes": wbytes,
+        "weights_gbs_in_gemm_kernels": wbytes / (gu_s + dn_s) / 1e9, "hbm_frac_in_gemm_kernels": wbytes / (gu_s + dn_s) / 1e9 / HBM_PEAK_GBS,
+        "weights_gbs_whole_step": wbytes / (r["wall_s"] / 400) / 1e9,
+        "stage_us": {k: float(v) * 1e3 for k, v in zip(zeda.STAGES, r["stage_ms"])},
+        "z0_ms_per_step": r0["wall_s"] / 400 * 1e3, "speedup_vs_z0": r0["wall_s"] / r["wall_s"]}
+    del L, L0
+    torch.cuda.empty_cache()
+    # configuration 4: heterogeneous prefill, the compute-bound regime of the grouped GEMMs
+    w = synth.CONFIGS["c4_hetero_prefill"]
+    L = synth.make_layer(w, "cuda")
+    L = pack_layer(w, L) if tiled else L
+    r = run_layer(w, L, steps=150, warmup=100)
+    w0, L0 = static_twin(w, L)
+    r0 = run_layer(w0, L0, steps=80, warmup=40)
+    gu_s, dn_s = r["stage_ms"][2] * 1e-3, r["stage_ms"][3] * 1e-3
+    gu_f, dn_f = 4.0 * w.H * w.I * r["R"], 2.0 * w.H * w.I * r["R"]
+    legs["c4_hetero_prefill"] = {
+        "T": w.T, "ms_per_step": r["wall_s"] / 150 * 1e3, "tokens_per_s": w.T * 150 / r["wall_s"],
+        "real_slots": r["R"], "r_ze": 1.0 - r["R"] / (w.T * w.K), "max_rows_per_expert": r["max_rows"],
+        "gateup_tflops": gu_f / gu_s / 1e12, "down_tflops": dn_f / dn_s / 1e12,
+        "gateup_mfma_frac": gu_f / gu_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "expert_gemm_mfma_frac": (gu_f + dn_f) / (gu_s + dn_s) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "stage_us": {k: float(v) * 1e3 for k, v in zip(zeda.STAGES, r["stage_ms"])},
+        "z0_ms_per_step": r0["wall_s"] / 80 * 1e3, "speedup_vs_z0": (r0["wall_s"] / 80) / (r["wall_s"] / 150),
+        "expert_flop_reduction": 1.0 - r["R"] / max(1, r0["R"])}
+    del L, L0
+    torch.cuda.empty_cache()
+    # configuration 5: the 48-layer chain with and without zero experts
+    _, legs["c5_stack"] = time_stack(48, steps=12, warmup=3, tiled=tiled)
+    return legs
 
 
 def main() -> int:
@@ -125,6 +198,8 @@ def main() -> int:
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters; outside the timed region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-z0", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short legs of configurations 3, 4 and 5 that the default run adds after the headline")
     ap.add_argument("--library-gemm", action="store_true",
                     help="context: also time torch.bmm (the vendor GEMM library) on dense batched GEMMs of the expert "
                          "GEMMs' shapes (no gather, no SwiGLU, every expert with the mean row count)")
@@ -161,10 +236,7 @@ def main() -> int:
     L_rowmajor = L
     if a.weights == "tiled" and w.dtype == "bf16":
         # weights are static: packed once, outside the timed region, as when a model is loaded
-        L = dict(L)
-        L["w_gate"], L["w_up"], L["w_down"] = zeda.zeda_pack_expert_weights(
-            zeda.make_desc(w.T, w.H, w.I, w.N, w.Z, w.K, w.dtype), L["w_gate"], L["w_up"], L["w_down"])
-        L["weight_layout"] = zeda.WEIGHTS_TILED
+        L = pack_layer(w, L)
     torch.cuda.synchronize()
     r = run_layer(w, L, a.steps, a.warmup)
     ms = r["wall_s"] / a.steps * 1e3
@@ -219,10 +291,7 @@ def main() -> int:
 
     if not a.no_z0 and w.Z > 0:
         # the same kernels on the static layer: no zero experts, top-K over the N normal experts only
-        w0 = w.with_(Z=0, recipe="plain")
-        L0 = dict(L)
-        L0["w_router"] = L["w_router"][: w.N].contiguous()
-        L0["router_bias"] = None
+        w0, L0 = static_twin(w, L)
         r0 = run_layer(w0, L0, a.steps, a.warmup)
         res["z0"] = {"ms_per_step": r0["wall_s"] / a.steps * 1e3, "speedup_vs_z0": r0["wall_s"] / r["wall_s"],
                      "real_slots": r0["R"], "expert_flop_reduction": 1.0 - R / max(1, r0["R"]),
@@ -248,6 +317,9 @@ def main() -> int:
             lib[name] = {"us": dt * 1e6, "tflops": 2.0 * ne * m * kd * nd / dt / 1e12, "batch": ne, "rows": m}
             del A, B, C
         res["library_gemm"] = lib
+
+    if w.name == "c2_qwen_prefill" and a.tokens <= 0 and not a.no_other_configs:
+        res["other_configs"] = other_config_legs(a.weights == "tiled")
 
     if not a.no_cpu_baseline:
         from oracle import harness, zeda_oracle as orc  # CPU-baseline leg only

@@ -35,6 +35,23 @@ class MoeStack:
         self.y = torch.empty((ww.T, ww.H), dtype=ww.torch_dtype, device=device)
         self.num_real = torch.zeros(layers, dtype=torch.int32, device=device)
 
+    def static_twin(self) -> "MoeStack":
+        """The same stack without zero experts (router restricted to the normal experts, no bias), sharing this
+        stack's expert weights and, being run one after the other, its scratch."""
+        if self.w.Z == 0:
+            return self
+        twin = object.__new__(MoeStack)
+        twin.w = self.w.with_(Z=0, recipe="plain")
+        twin.layers = self.layers
+        twin.weights = [dict(p, w_router=p["w_router"][: self.w.N].contiguous(), router_bias=None) for p in self.weights]
+        twin.desc = zeda.make_desc(twin.w.T, twin.w.H, twin.w.I, twin.w.N, 0, twin.w.K, twin.w.dtype,
+                                   weight_layout=self.desc.weight_layout)
+        need = zeda.workspace_bytes(twin.desc)
+        twin.ws = self.ws if self.ws.numel() >= need else torch.empty(need, dtype=torch.uint8, device=self.ws.device)
+        twin.xn, twin.y = self.xn, self.y
+        twin.num_real = torch.zeros_like(self.num_real)
+        return twin
+
     def forward(self, x: torch.Tensor, hook=None, fused: Optional[bool] = None) -> torch.Tensor:
         """Runs the chain in place on x (the residual stream) and returns it.  The stream is never synchronised.
         fused (default: whenever no hook is given): one zeda_moe_block_forward per layer, whose combine stage adds
