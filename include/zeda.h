@@ -125,6 +125,20 @@ int zeda_dispatch(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t 
                   int32_t *sorted_slot /*[T*K]*/, int32_t *slot_to_row /*[T*K]*/, int32_t *num_real /*[1]*/,
                   void *ws, size_t ws_bytes, void *stream);
 
+/* zeda_dispatch for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and results as zeda_dispatch; the
+ * scratch (the per-segment counts of long slot lists) is a 256 KiB array that the library itself holds in each
+ * GPU's memory from load time to the end of the process.  The call allocates and frees nothing.
+ * Limit: T*K <= zeda_dispatch_noalloc_max_slots() (524288), ZEDA_EUNSUPPORTED beyond it.
+ * Nothing in the scratch has to start at zero (the counts a call reads are the ones it has just written).
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different streams,
+ * different host threads) race; order them.  The array's device address is looked up on the first call on each
+ * device (a runtime query: make that first call outside stream capture); ZEDA_EHIP if the lookup fails. */
+int zeda_dispatch_noalloc_max_slots(void);
+int zeda_dispatch_noalloc(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t *expert_offsets /*[N+1]*/,
+                          int32_t *sorted_slot /*[T*K]*/, int32_t *slot_to_row /*[T*K]*/, int32_t *num_real /*[1]*/,
+                          void *stream);
+
 /* Grouped SwiGLU expert FFN over the real slots only (Appendix D, Eq. 10: 6*H*I FLOPs per real slot):
  *   y_slot[r,:] = E_e(x[sorted_slot[r] / K, :])  for expert_offsets[e] <= r < expert_offsets[e+1].
  * Work is launched for non-empty experts only.  y_slot has room for T*K rows of H elements of

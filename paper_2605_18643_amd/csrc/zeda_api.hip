@@ -202,6 +202,26 @@ int zeda_dispatch(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t 
                            (hipStream_t)stream);
 }
 
+int zeda_dispatch_noalloc_max_slots(void) { return dispatch_static_max_slots(); }
+
+int zeda_dispatch_noalloc(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t *expert_offsets,
+                          int32_t *sorted_slot, int32_t *slot_to_row, int32_t *num_real, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != ZEDA_OK) return rc;
+    if (!topk_ids || !expert_offsets || !sorted_slot || !slot_to_row || !num_real) return ZEDA_EINVAL;
+    if (!aligned16(topk_ids) || !aligned16(expert_offsets) || !aligned16(sorted_slot) || !aligned16(slot_to_row) ||
+        (reinterpret_cast<uintptr_t>(num_real) & 3u))
+        return ZEDA_EINVAL;
+    // the library's own scratch is sized for the segmented form's longest list
+    if ((int64_t)desc->T * desc->K > dispatch_static_max_slots()) return ZEDA_EUNSUPPORTED;
+    if (dispatch_ws_bytes(desc) > dispatch_static_scratch_bytes()) return ZEDA_EUNSUPPORTED;
+    void *ws = dispatch_static_scratch();
+    if (!ws) return ZEDA_EHIP;
+    return launch_dispatch(desc, topk_ids, expert_offsets, sorted_slot, slot_to_row, num_real, nullptr, ws,
+                           (hipStream_t)stream);
+}
+
 int zeda_expert_ffn(const zeda_layer_desc *desc, const void *x, const void *w_gate, const void *w_up,
                     const void *w_down, const int32_t *expert_offsets, const int32_t *sorted_slot,
                     const int32_t *num_real, void *y_slot, void *ws, size_t ws_bytes, void *stream)

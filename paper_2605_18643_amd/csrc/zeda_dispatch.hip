@@ -269,6 +269,29 @@ size_t dispatch_ws_bytes(const zeda_layer_desc *d)
     return align_up(segments * d->N * sizeof(int32_t), 256);
 }
 
+// Library-owned scratch of zeda_dispatch_noalloc: the per-segment counts of the segmented form at its largest
+// (kSegMax segments x kMaxExperts experts).  One copy per GPU, held until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the device address it returns is what kernels get.
+constexpr size_t kStaticScratchBytes = (size_t)kSegMax * kMaxExperts * sizeof(int32_t);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+size_t dispatch_static_scratch_bytes() { return kStaticScratchBytes; }
+int dispatch_static_max_slots() { return kSegMax * kSegSlots; }
+
+// device address of `scratch` on the calling thread's current device (looked up once per device), or NULL
+void *dispatch_static_scratch()
+{
+    static void *ptrs[kMaxDevices] = {};  // idempotent per device, so a race between host threads is harmless
+    const int dev = current_device();
+    if (dev < 0) return nullptr;
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        ptrs[dev] = p;
+    }
+    return ptrs[dev];
+}
+
 int launch_dispatch(const zeda_layer_desc *d, const int32_t *ids, int32_t *offsets, int32_t *sorted_slot,
                     int32_t *slot_to_row, int32_t *num_real, int32_t *num_real_copy, void *ws, hipStream_t s)
 {

@@ -45,6 +45,10 @@ size_t routing_stats_ws_bytes(const zeda_layer_desc *d);
 int launch_dispatch(const zeda_layer_desc *d, const int32_t *ids, int32_t *offsets, int32_t *sorted_slot,
                     int32_t *slot_to_row, int32_t *num_real, int32_t *num_real_copy, void *ws, hipStream_t s);
 size_t dispatch_ws_bytes(const zeda_layer_desc *d);
+// scratch held by the library itself (a file-scope device array) for zeda_dispatch_noalloc
+void *dispatch_static_scratch();          // its address on the current device, NULL if the lookup fails
+size_t dispatch_static_scratch_bytes();
+int dispatch_static_max_slots();          // slot lists up to this length are accepted by that entry point
 int launch_gateup(const zeda_layer_desc *d, const void *x, const void *wg, const void *wu, const int32_t *offsets,
                   const int32_t *sorted_slot, void *act, hipStream_t s);
 int launch_down(const zeda_layer_desc *d, const void *act, const void *wd, const int32_t *offsets, void *y_slot,

@@ -23,6 +23,7 @@ STAGES = ("route", "dispatch", "gateup", "down", "combine")
 
 EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_route_workspace_bytes", "zeda_dispatch_workspace_bytes",
            "zeda_expert_ffn_workspace_bytes", "zeda_workspace_layout", "zeda_route", "zeda_dispatch",
+           "zeda_dispatch_noalloc", "zeda_dispatch_noalloc_max_slots",
            "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events", "zeda_moe_block_forward",
            "zeda_rmsnorm",
            "zeda_residual_add", "zeda_pack_expert_weights", "zeda_routing_stats_workspace_bytes", "zeda_routing_stats",
@@ -70,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.zeda_route.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.zeda_dispatch.restype = i32
         L.zeda_dispatch.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.zeda_dispatch_noalloc.restype = i32
+        L.zeda_dispatch_noalloc.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+        L.zeda_dispatch_noalloc_max_slots.restype = i32
+        L.zeda_dispatch_noalloc_max_slots.argtypes = []
         L.zeda_expert_ffn.restype = i32
         L.zeda_expert_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.zeda_combine.restype = i32
@@ -153,6 +158,16 @@ def zeda_dispatch(desc, topk_ids, expert_offsets, sorted_slot, slot_to_row, num_
     _check(lib().zeda_dispatch(ctypes.byref(desc), _ptr(topk_ids), _ptr(expert_offsets), _ptr(sorted_slot),
                                _ptr(slot_to_row), _ptr(num_real), _ptr(ws), ws.numel() * ws.element_size(),
                                _stream(stream)), "zeda_dispatch")
+
+
+def zeda_dispatch_noalloc(desc, topk_ids, expert_offsets, sorted_slot, slot_to_row, num_real, stream=None) -> None:
+    """zeda_dispatch on the library's own static scratch (no workspace argument, nothing allocated)."""
+    _check(lib().zeda_dispatch_noalloc(ctypes.byref(desc), _ptr(topk_ids), _ptr(expert_offsets), _ptr(sorted_slot),
+                                       _ptr(slot_to_row), _ptr(num_real), _stream(stream)), "zeda_dispatch_noalloc")
+
+
+def dispatch_noalloc_max_slots() -> int:
+    return int(lib().zeda_dispatch_noalloc_max_slots())
 
 
 def zeda_expert_ffn(desc, x, w_gate, w_up, w_down, expert_offsets, sorted_slot, num_real, y_slot, ws,
