@@ -29,6 +29,10 @@ static size_t act_bytes(const zeda_layer_desc *d)
     return align_up((size_t)d->T * d->K * d->I * elt_size(d), 256);
 }
 
+// The whole-layer call has the router leave per-block expert counts and places from them, where both apply.
+static bool fused_counts(const zeda_layer_desc *d) { return route_counts_supported(d) && dispatch_counts_supported(d); }
+static size_t fused_counts_bytes(const zeda_layer_desc *d) { return fused_counts(d) ? route_counts_bytes(d) : 0; }
+
 static void layout_of(const zeda_layer_desc *d, zeda_ws_layout *L)
 {
     const size_t S = (size_t)d->T * d->K;
@@ -40,7 +44,8 @@ static void layout_of(const zeda_layer_desc *d, zeda_ws_layout *L)
     L->sorted_slot = take(S * 4);
     L->slot_to_row = take(S * 4);
     L->num_real = take(4);
-    L->dispatch_ws = take(dispatch_ws_bytes(d));
+    // (the whole-layer call keeps the router's per-block counts here when it uses them instead of the counting pass)
+    L->dispatch_ws = take(dispatch_ws_bytes(d) > fused_counts_bytes(d) ? dispatch_ws_bytes(d) : fused_counts_bytes(d));
     L->act = take(act_bytes(d));
     L->y_slot = take(S * d->H * elt_size(d));
     L->route_ws = take(route_ws_bytes(d));
@@ -104,9 +109,16 @@ static int forward_impl(const zeda_layer_desc *desc, const void *x, const void *
         for (int i = 1; i <= ZEDA_NUM_STAGES; ++i) mark(i);
         return rc;
     }
-    if ((rc = launch_route(desc, x, w_router, router_bias, ids, gates, route_ws, s)) != ZEDA_OK) return rc;
-    mark(1 + ZEDA_STAGE_ROUTE);
-    if ((rc = launch_dispatch(desc, ids, offsets, sorted_slot, slot_to_row, num_real, num_real_out, w + L.dispatch_ws, s)) != ZEDA_OK) return rc;
+    if (fused_counts(desc)) {
+        uint8_t *cnt8 = (uint8_t *)(w + L.dispatch_ws);
+        if ((rc = launch_route(desc, x, w_router, router_bias, ids, gates, route_ws, cnt8, s)) != ZEDA_OK) return rc;
+        mark(1 + ZEDA_STAGE_ROUTE);
+        if ((rc = launch_dispatch_counts(desc, ids, cnt8, offsets, sorted_slot, slot_to_row, num_real, num_real_out, s)) != ZEDA_OK) return rc;
+    } else {
+        if ((rc = launch_route(desc, x, w_router, router_bias, ids, gates, route_ws, nullptr, s)) != ZEDA_OK) return rc;
+        mark(1 + ZEDA_STAGE_ROUTE);
+        if ((rc = launch_dispatch(desc, ids, offsets, sorted_slot, slot_to_row, num_real, num_real_out, w + L.dispatch_ws, s)) != ZEDA_OK) return rc;
+    }
     mark(1 + ZEDA_STAGE_DISPATCH);
     if ((rc = launch_gateup(desc, x, w_gate, w_up, offsets, sorted_slot, act, s)) != ZEDA_OK) return rc;
     mark(1 + ZEDA_STAGE_GATEUP);
@@ -185,7 +197,7 @@ int zeda_route(const zeda_layer_desc *desc, const void *x, const void *w_router,
     if (ws && ws_bytes < route_ws_bytes(desc)) return ZEDA_EWORKSPACE;
     if (desc->T == 0) return ZEDA_OK;
     float *partial = (ws && route_ws_bytes(desc)) ? (float *)ws : nullptr;
-    return launch_route(desc, x, w_router, router_bias, topk_ids, topk_gates, partial, (hipStream_t)stream);
+    return launch_route(desc, x, w_router, router_bias, topk_ids, topk_gates, partial, nullptr, (hipStream_t)stream);
 }
 
 int zeda_dispatch(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t *expert_offsets, int32_t *sorted_slot,

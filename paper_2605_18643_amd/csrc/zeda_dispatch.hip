@@ -262,6 +262,128 @@ __global__ __launch_bounds__(kSegThreads) void dispatch_place_kernel(const int32
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// placement from the router's per-block counts
+// ---------------------------------------------------------------------------------------------
+// The router kernel that holds its token rows in LDS leaves, per block of 16 tokens, the number of slots on every
+// expert (one byte each, cnt8[e][block]).  With those the placement needs no counting pass over the ids and no
+// second kernel: a workgroup takes 64 tokens (4 blocks, 64*K slots, one 64-slot group per wave), adds up, per
+// expert, the bytes of all blocks (the expert's rows) and of the blocks before its own (the rows before its
+// segment) - four threads per expert, 16 blocks per 16-byte load, v_sad_u8 adding four bytes at a time - scans
+// the totals over the experts, and places its slots as the segmented form above does.
+constexpr int kCntTokens = 64;     // tokens per workgroup: 4 blocks of the router
+constexpr int kCntThreads = 1024;  // 16 waves: K <= 16 groups of 64 slots
+constexpr int kCntMaxTokens = 16384;  // beyond this the tables every workgroup adds up get long: the forms above take over
+static_assert(kCntThreads / 64 >= kMaxK && kCntThreads / kMaxExperts == 4, "one wave per 64-slot group, four threads per expert");
+
+__global__ __launch_bounds__(kCntThreads) void dispatch_place_counts_kernel(const int32_t *__restrict__ ids, int S, int N, int K,
+                                                                            const uint8_t *__restrict__ cnt8, int cnt_ld, int nblk,
+                                                                            int32_t *__restrict__ expert_offsets,
+                                                                            int32_t *__restrict__ sorted_slot,
+                                                                            int32_t *__restrict__ slot_to_row,
+                                                                            int32_t *__restrict__ num_real,
+                                                                            int32_t *__restrict__ num_real_copy)
+{
+    __shared__ int s_cnt[kMaxK][kMaxExperts];  // slots of wave w's group on every expert, then the running rows
+    __shared__ int s_tot[4][kMaxExperts], s_bef[4][kMaxExperts];
+    __shared__ int s_first[kMaxExperts];
+    __shared__ int s_wsum[kMaxExperts / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, seg = blockIdx.x;
+    for (int i = tid; i < kMaxK * kMaxExperts; i += kCntThreads) (&s_cnt[0][0])[i] = 0;
+    __syncthreads();
+    // this wave's group of 64 slots
+    const int s = seg * (kCntTokens * K) + wave * 64 + lane;
+    const bool in_seg = wave < K && s < S;
+    const int id = in_seg ? ids[s] : -1;
+    const bool real = (unsigned)id < (unsigned)N;
+    const unsigned long long m = same_expert_lanes(id, real);
+    const int rank = __popcll(m & ((1ull << lane) - 1ull));
+    if (real && rank == 0) s_cnt[wave][id] = __popcll(m);
+
+    // thread (e, part): rows of expert e in a quarter of the blocks, and in those of them before this segment
+    {
+        const int e = tid & (kMaxExperts - 1), part = tid >> 8;
+        int total = 0, before = 0;
+        if (e < N) {
+            const int words = cnt_ld / 16, per = (words + 3) / 4;  // 16-byte words of the expert's row of bytes
+            const uint4 *row = reinterpret_cast<const uint4 *>(cnt8 + (size_t)e * cnt_ld);
+            const int first_blk = seg * (kCntTokens / 16);
+            for (int wi = part * per; wi < min(words, (part + 1) * per); ++wi) {
+                const uint4 v = row[wi];
+                const unsigned dw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int b0 = wi * 16 + q * 4;  // blocks b0 .. b0+3
+                    unsigned x = dw[q];
+                    if (b0 + 4 > nblk) x = b0 >= nblk ? 0u : (x & ((1u << (8 * (nblk - b0))) - 1u));  // bytes past the last block
+                    const int c = (int)__builtin_amdgcn_sad_u8(x, 0u, 0u);
+                    total += c;
+                    before += b0 < first_blk ? c : 0;  // (segments start at multiples of four blocks)
+                }
+            }
+        }
+        s_tot[part][e] = total;
+        s_bef[part][e] = before;
+    }
+    __syncthreads();
+    int total = 0, before = 0;
+    if (tid < kMaxExperts) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { total += s_tot[q][tid]; before += s_bef[q][tid]; }
+        // exclusive scan of the totals over the experts
+        int incl = total;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(incl, o);
+            if (lane >= o) incl += v;
+        }
+        if (lane == 63) s_wsum[wave] = incl;
+        s_first[tid] = incl - total;
+    }
+    __syncthreads();
+    if (tid < kMaxExperts) {
+        int add = 0;
+        for (int w = 0; w < wave; ++w) add += s_wsum[w];
+        const int first_row = s_first[tid] + add;
+        if (seg == 0 && tid < N) expert_offsets[tid] = first_row;
+        if (seg == 0 && tid == N - 1) {
+            const int R = first_row + total;
+            expert_offsets[N] = R;
+            num_real[0] = R;
+            if (num_real_copy) num_real_copy[0] = R;
+        }
+        // running row of (wave, expert): the expert's first row, the segments before, the waves before
+        int row = first_row + before;
+        if (tid < N) {
+            for (int w = 0; w < K; ++w) {
+                const int c = s_cnt[w][tid];
+                s_cnt[w][tid] = row;
+                row += c;
+            }
+        }
+    }
+    __syncthreads();
+    if (real) {
+        const int r = s_cnt[wave][id] + rank;
+        sorted_slot[r] = s;
+        slot_to_row[s] = r;
+    } else if (in_seg) {
+        slot_to_row[s] = -1;
+    }
+}
+
+bool dispatch_counts_supported(const zeda_layer_desc *d) { return d->T <= kCntMaxTokens; }
+
+int launch_dispatch_counts(const zeda_layer_desc *d, const int32_t *ids, const uint8_t *cnt8, int32_t *offsets,
+                           int32_t *sorted_slot, int32_t *slot_to_row, int32_t *num_real, int32_t *num_real_copy,
+                           hipStream_t s)
+{
+    const int S = d->T * d->K, nblk = ceil_div(d->T, 16);
+    dispatch_place_counts_kernel<<<ceil_div(d->T, kCntTokens), kCntThreads, 0, s>>>(
+        ids, S, d->N, d->K, cnt8, route_counts_ld(d), nblk, offsets, sorted_slot, slot_to_row, num_real, num_real_copy);
+    return last_launch_status();
+}
+
 size_t dispatch_ws_bytes(const zeda_layer_desc *d)
 {
     const size_t S = (size_t)d->T * d->K, segments = (S + kSegSlots - 1) / kSegSlots;

@@ -34,9 +34,20 @@ inline size_t elt_size(const zeda_layer_desc *d) { return d->dtype == ZEDA_BF16 
 
 // stage launchers: arguments are already validated; each returns ZEDA_OK or ZEDA_EHIP
 // partial: scratch of route_ws_bytes(d) for the split-k launch, or NULL (one kernel, no scratch)
+// cnt8: route_counts_bytes(d) of scratch that receives the per-block expert counts, or NULL (bf16 only)
 int launch_route(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
-                 float *gates, float *partial, hipStream_t s);
+                 float *gates, float *partial, uint8_t *cnt8, hipStream_t s);
 size_t route_ws_bytes(const zeda_layer_desc *d);
+// Per-block expert counts of the bf16 router: cnt8 [N+Z][route_counts_ld(d)] bytes receive, per block of 16 tokens,
+// the number of slots on every expert - what launch_dispatch_counts starts from.
+bool route_counts_supported(const zeda_layer_desc *d);
+int route_counts_ld(const zeda_layer_desc *d);
+size_t route_counts_bytes(const zeda_layer_desc *d);
+// expert-sorted placement that starts from those per-block counts instead of counting the ids again
+bool dispatch_counts_supported(const zeda_layer_desc *d);
+int launch_dispatch_counts(const zeda_layer_desc *d, const int32_t *ids, const uint8_t *cnt8, int32_t *offsets,
+                           int32_t *sorted_slot, int32_t *slot_to_row, int32_t *num_real, int32_t *num_real_copy,
+                           hipStream_t s);
 // Section 2.2 statistics over the batch of all T tokens (f, P: [N+Z]; summary: 7 floats); ws of routing_stats_ws_bytes
 int launch_routing_stats(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, float alpha, float w,
                          float *f, float *P, float *summary, void *ws, hipStream_t s);

@@ -70,10 +70,14 @@ __device__ __forceinline__ float wave_sum(float v)
 // candidates l, l + 16, ... (NC of them).  One round: the row maximum, then the lowest expert index among the
 // candidates equal to it (ties go to the lower index), which its owner then removes.  Lane j of the row keeps
 // slot j, so lanes 0..K-1 end up with the slots in descending-logit order (K <= 16).
+// Returns the expert of the slot this lane keeps (lane j < K of a row: slot j of the row's token), or -1.
+// probs (may be NULL): an LDS table [token][LDP] that receives, for every token of the wave, the routing
+// probability of every expert (softmax over all NE logits).
 template <int NC, int NP>
-__device__ __forceinline__ void select_rows(const float *lg, int LD, int pstride, int np_rt, const float *__restrict__ bias, int tk0,
-                                            int ntok, int t0, int T, int NE, int N, int K, int gate_norm,
-                                            int32_t *__restrict__ ids, float *__restrict__ gates)
+__device__ __forceinline__ int select_rows(const float *lg, int LD, int pstride, int np_rt, const float *__restrict__ bias, int tk0,
+                                           int ntok, int t0, int T, int NE, int N, int K, int gate_norm,
+                                           int32_t *__restrict__ ids, float *__restrict__ gates, float *probs = nullptr,
+                                           int LDP = 0)
 {
     const int lane = threadIdx.x & 63, l16 = lane & 15, tk = tk0 + (lane >> 4);
     const bool ok = tk < ntok && t0 + tk < T;
@@ -99,11 +103,19 @@ __device__ __forceinline__ void select_rows(const float *lg, int LD, int pstride
     };
     const float all_max = row_max(local_max());
     float all_sum = 0.f;
-    if (gate_norm == ZEDA_GATE_SOFTMAX) {
-        float sacc = 0.f;
+    if (gate_norm == ZEDA_GATE_SOFTMAX || probs) {
+        float ex[NC], sacc = 0.f;
 #pragma unroll
-        for (int c = 0; c < NC; ++c) sacc += (l16 + 16 * c < NE) ? expf(cand[c] - all_max) : 0.f;
+        for (int c = 0; c < NC; ++c) {
+            ex[c] = (ok && l16 + 16 * c < NE) ? expf(cand[c] - all_max) : 0.f;
+            sacc += ex[c];
+        }
         all_sum = row_sum(sacc);
+        if (probs && ok) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                if (l16 + 16 * c < NE) probs[tk * LDP + l16 + 16 * c] = ex[c] / all_sum;
+        }
     }
     int my_id = 0;
     float my_logit = -INFINITY;
@@ -125,23 +137,51 @@ __device__ __forceinline__ void select_rows(const float *lg, int LD, int pstride
     if (gate_norm == ZEDA_GATE_SOFTMAX) dn = all_sum;
     else if (gate_norm == ZEDA_GATE_TOPK_NORM) dn = row_sum(ex);
     else dn = row_sum((slot && my_id < N) ? ex : 0.f);
-    if (slot && ok) {
+    if (slot && ok && ids) {
         const size_t o = (size_t)(t0 + tk) * K + l16;
         ids[o] = my_id;
         gates[o] = dn > 0.f ? ex / dn : 0.f;
     }
+    return (slot && ok) ? my_id : -1;
 }
 
 // All ntok tokens of a workgroup of NWAVES waves, four per wave at a time.  lg holds NP partial logit tables
 // pstride floats apart.
+// s_cnt (LDS, may be NULL): [ntok / 16][kMaxExperts] counters, zeroed by the caller; every selected slot adds one to
+// the counter of its expert in its block of 16 tokens (the counts do not depend on the order of the additions).
+// probs (LDS, may be NULL): [ntok][LDP] table that receives every token's routing probabilities.
 template <int NC, int NP, int NWAVES>
 __device__ __forceinline__ void select_block(const float *lg, int LD, int pstride, int np_rt, const float *__restrict__ bias, int ntok,
                                              int t0, int T, int NE, int N, int K, int gate_norm, int32_t *__restrict__ ids,
-                                             float *__restrict__ gates)
+                                             float *__restrict__ gates, int *s_cnt = nullptr, float *probs = nullptr,
+                                             int LDP = 0)
 {
     const int wave = threadIdx.x >> 6;
-    for (int tk0 = 4 * wave; tk0 < ntok; tk0 += 4 * NWAVES)
-        select_rows<NC, NP>(lg, LD, pstride, np_rt, bias, tk0, ntok, t0, T, NE, N, K, gate_norm, ids, gates);
+    for (int tk0 = 4 * wave; tk0 < ntok; tk0 += 4 * NWAVES) {
+        const int id = select_rows<NC, NP>(lg, LD, pstride, np_rt, bias, tk0, ntok, t0, T, NE, N, K, gate_norm, ids, gates, probs, LDP);
+        if (s_cnt && id >= 0) atomicAdd(&s_cnt[(tk0 >> 4) * kMaxExperts + id], 1);
+    }
+}
+
+// After select_block (and a barrier): what the workgroup's blocks of 16 tokens hand to the expert-sorted placement
+// and to the routing statistics.  cnt8[e][cnt_ld] bytes: slots of every block on expert e; p_part[block][NE]: the
+// block's sum of every expert's routing probability, added in token order.
+template <int THREADS>
+__device__ __forceinline__ void publish_blocks(const int *s_cnt, const float *probs, int LDP, int ntok, int t0, int T, int NE,
+                                               uint8_t *__restrict__ cnt8, int cnt_ld, float *__restrict__ p_part)
+{
+    const int nblk = (ntok + 15) >> 4;
+    for (int i = threadIdx.x; i < nblk * NE; i += THREADS) {
+        const int u = i / NE, e = i - u * NE, blk = (t0 >> 4) + u;
+        if (t0 + u * 16 >= T) continue;
+        if (cnt8) cnt8[(size_t)e * cnt_ld + blk] = (uint8_t)s_cnt[u * kMaxExperts + e];
+        if (p_part) {
+            float ps = 0.f;
+            const int nt = min(16, min(ntok, T - t0) - u * 16);
+            for (int t = 0; t < nt; ++t) ps += probs[(u * 16 + t) * LDP + e];
+            p_part[(size_t)blk * NE + e] = ps;
+        }
+    }
 }
 
 // bf16 router.  A workgroup owns kRouteTokens tokens and all NE experts (NB MFMA row blocks of 32; tokens
@@ -175,7 +215,9 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
                                                                    const float *__restrict__ bias, int T, int H, int N,
                                                                    int NE, int K, int gate_norm,
                                                                    int32_t *__restrict__ ids, float *__restrict__ gates,
-                                                                   float *__restrict__ partial, int Tpad)
+                                                                   float *__restrict__ partial, int Tpad,
+                                                                   uint8_t *__restrict__ cnt8, int cnt_ld,
+                                                                   float *__restrict__ p_part)
 {
     constexpr int TOK = 32 * TB;                  // tokens of the workgroup
     constexpr int LD = NB * 32 + 1;
@@ -184,8 +226,10 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
     constexpr int NL = TB + NB;                   // wave load instructions (8 rows each) per chunk and wave
     constexpr int kRouteStages = route_stages(NB, TB);
     constexpr int NT = 4 / TB;                    // partial logit tables in LDS (the four waves' sums meet in them)
+    static_assert(kRouteThreads == kMaxExperts, "");
     static_assert(kRouteTokens == 32 && kRouteThreads == 256 && (TB == 1 || TB == 2), "token blocks of 32, four waves");
-    static_assert(NT * TOK * LD * 4 <= kRouteStages * STAGE, "the partial logit tables reuse the ring");
+    static_assert(NT * TOK * LD * 4 + (TOK / 16) * kMaxExperts * 4 <= kRouteStages * STAGE,
+                  "the partial logit tables and the per-block expert counters reuse the ring");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     float *lg = reinterpret_cast<float *>(lds);
 
@@ -272,7 +316,20 @@ __global__ __launch_bounds__(kRouteThreads) void route_bf16_kernel(const bf16_t 
         __syncthreads();
     }
     if (partial == nullptr) {
-        select_block<2 * NB, NT, 4>(lg, LD, TOK * LD, NT, bias, TOK, t0, T, NE, N, K, gate_norm, ids, gates);
+        // cnt8, p_part (either may be NULL): per block of 16 tokens, the slots on every expert (for the expert-sorted
+        // placement) and the sums of the routing probabilities (routing statistics), see publish_blocks.  The
+        // probabilities of a token overwrite its row of the first logit table once the token's logits are in registers.
+        int *s_cnt = reinterpret_cast<int *>(lg + NT * TOK * LD);
+        if (cnt8) {
+            for (int i = tid; i < (TOK / 16) * kMaxExperts; i += kRouteThreads) s_cnt[i] = 0;
+            __syncthreads();
+        }
+        select_block<2 * NB, NT, 4>(lg, LD, TOK * LD, NT, bias, TOK, t0, T, NE, N, K, gate_norm, ids, gates,
+                                    cnt8 ? s_cnt : nullptr, p_part ? lg : nullptr, LD);
+        if (cnt8 || p_part) {
+            __syncthreads();
+            publish_blocks<kRouteThreads>(s_cnt, lg, LD, TOK, t0, T, NE, cnt8, cnt_ld, p_part);
+        }
     } else {
         // split-k launch: this workgroup's sums over its slice (the tables added in order) go to
         // partial[blockIdx.y][token][expert]; route_select_kernel adds the slices in order and selects
@@ -293,12 +350,26 @@ template <int NB, int NSPLIT>
 __global__ __launch_bounds__(kRouteThreads) void route_select_kernel(const float *__restrict__ partial, int Tpad,
                                                                      const float *__restrict__ bias, int T, int N, int NE,
                                                                      int K, int gate_norm, int32_t *__restrict__ ids,
-                                                                     float *__restrict__ gates)
+                                                                     float *__restrict__ gates, uint8_t *__restrict__ cnt8,
+                                                                     int cnt_ld, float *__restrict__ p_part)
 {
+    static_assert(kSelectTokens == 16, "one block of the per-block tables per workgroup");
+    constexpr int LDP = NB * 32 + 1;
+    __shared__ int s_cnt[kMaxExperts];
+    __shared__ float s_probs[kSelectTokens * LDP];  // (used by the statistics run only)
     const int t0 = blockIdx.x * kSelectTokens;
+    if (cnt8) {
+        s_cnt[threadIdx.x] = 0;  // (kRouteThreads == kMaxExperts)
+        __syncthreads();
+    }
     // (the number of slices is a template parameter so that all loads of a lane's candidates are issued together)
     select_block<2 * NB, NSPLIT, 4>(partial + (size_t)t0 * (NB * 32), NB * 32, Tpad * NB * 32, NSPLIT, bias, kSelectTokens,
-                                    t0, T, NE, N, K, gate_norm, ids, gates);
+                                    t0, T, NE, N, K, gate_norm, ids, gates, cnt8 ? s_cnt : nullptr,
+                                    p_part ? s_probs : nullptr, LDP);
+    if (cnt8 || p_part) {
+        __syncthreads();
+        publish_blocks<kRouteThreads>(s_cnt, s_probs, LDP, kSelectTokens, t0, T, NE, cnt8, cnt_ld, p_part);
+    }
 }
 
 // fp32 router (plain FMA): a workgroup owns 8 tokens staged in LDS chunk by chunk; a wave walks the
@@ -390,16 +461,23 @@ static bool route_lds_opt_in(int lds_bytes)
     return true;
 }
 
+// Optional per-block outputs of a router launch (see publish_blocks); all NULL / 0 when not wanted.
+struct RouteExtras {
+    uint8_t *cnt8;
+    int cnt_ld;
+    float *p_part;
+};
+
 template <int NB>
 static int launch_route_bf16_wide(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias,
-                                  int32_t *ids, float *gates, hipStream_t s)
+                                  int32_t *ids, float *gates, const RouteExtras &ex, hipStream_t s)
 {
     const int blocks = ceil_div(d->T, 64);
     constexpr int lds_bytes = route_stages(NB, 2) * (64 + 32 * NB) * 128;
     if (!route_lds_opt_in<NB, 2>(lds_bytes)) return ZEDA_EHIP;
     route_bf16_kernel<NB, 2><<<dim3(blocks, 1), kRouteThreads, lds_bytes, s>>>(
         (const bf16_t *)x, (const bf16_t *)wr, bias, d->T, d->H, d->N, d->N + d->Z, d->K, d->gate_norm, ids, gates, nullptr,
-        blocks * 64);
+        blocks * 64, ex.cnt8, ex.cnt_ld, ex.p_part);
     return last_launch_status();
 }
 
@@ -407,10 +485,10 @@ constexpr int kRouteWideTokens = 12288;  // from here on the 64-token blocks alo
 
 template <int NB>
 static int launch_route_bf16(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
-                             float *gates, float *partial, hipStream_t s, bool logits_only = false)
+                             float *gates, float *partial, const RouteExtras &ex, hipStream_t s)
 {
     if constexpr (NB <= 6) {
-        if (!logits_only && d->T >= kRouteWideTokens) return launch_route_bf16_wide<NB>(d, x, wr, bias, ids, gates, s);
+        if (d->T >= kRouteWideTokens) return launch_route_bf16_wide<NB>(d, x, wr, bias, ids, gates, ex, s);
     }
     const int blocks = ceil_div(d->T, kRouteTokens), Tpad = blocks * kRouteTokens;
     const int c = partial ? route_ksplit(d) : 1;
@@ -418,24 +496,45 @@ static int launch_route_bf16(const zeda_layer_desc *d, const void *x, const void
     if (!route_lds_opt_in<NB, 1>(lds_bytes)) return ZEDA_EHIP;
     route_bf16_kernel<NB, 1><<<dim3(blocks, c), kRouteThreads, lds_bytes, s>>>(
         (const bf16_t *)x, (const bf16_t *)wr, bias, d->T, d->H, d->N, d->N + d->Z, d->K, d->gate_norm, ids, gates,
-        (c > 1 || logits_only) ? partial : nullptr, Tpad);
-    if (logits_only) return last_launch_status();
+        c > 1 ? partial : nullptr, Tpad, ex.cnt8, ex.cnt_ld, ex.p_part);
+    if (c == 1) return last_launch_status();
     const dim3 sgrid(ceil_div(d->T, kSelectTokens));
     const int NE = d->N + d->Z;
     if (c == 2)
-        route_select_kernel<NB, 2><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates);
+        route_select_kernel<NB, 2><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates, ex.cnt8, ex.cnt_ld, ex.p_part);
     else if (c == 4)
-        route_select_kernel<NB, 4><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates);
-    else if (c == 8)
-        route_select_kernel<NB, 8><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates);
+        route_select_kernel<NB, 4><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates, ex.cnt8, ex.cnt_ld, ex.p_part);
+    else
+        route_select_kernel<NB, 8><<<sgrid, kRouteThreads, 0, s>>>(partial, Tpad, bias, d->T, d->N, NE, d->K, d->gate_norm, ids, gates, ex.cnt8, ex.cnt_ld, ex.p_part);
     return last_launch_status();
 }
 
+static int launch_route_bf16_any(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
+                                 float *gates, float *partial, const RouteExtras &ex, hipStream_t s)
+{
+    switch (ceil_div(d->N + d->Z, 32)) {
+        case 1: return launch_route_bf16<1>(d, x, wr, bias, ids, gates, partial, ex, s);
+        case 2: return launch_route_bf16<2>(d, x, wr, bias, ids, gates, partial, ex, s);
+        case 3: return launch_route_bf16<3>(d, x, wr, bias, ids, gates, partial, ex, s);
+        case 4: return launch_route_bf16<4>(d, x, wr, bias, ids, gates, partial, ex, s);
+        case 5: return launch_route_bf16<5>(d, x, wr, bias, ids, gates, partial, ex, s);
+        case 6: return launch_route_bf16<6>(d, x, wr, bias, ids, gates, partial, ex, s);
+        case 7: return launch_route_bf16<7>(d, x, wr, bias, ids, gates, partial, ex, s);
+        default: return launch_route_bf16<8>(d, x, wr, bias, ids, gates, partial, ex, s);
+    }
+}
+
+int route_counts_ld(const zeda_layer_desc *d) { return (int)align_up((size_t)ceil_div(d->T, 16), 16); }
+size_t route_counts_bytes(const zeda_layer_desc *d) { return align_up((size_t)(d->N + d->Z) * route_counts_ld(d), 256); }
+bool route_counts_supported(const zeda_layer_desc *d) { return d->dtype == ZEDA_BF16; }
+
 // ---------------------------------------------------------------------------------------------
 // Batch routing statistics (Section 2.2, Eq. 4-6): f_i, P_i, the group sums and the forward values of the
-// two auxiliary losses, over all T tokens as the batch.  Three steps: logits (the router kernels above, writing
-// their tables to scratch), per-block sums (route_stats_kernel), one final workgroup (route_stats_final_kernel).
-// Every floating-point sum runs in a fixed order.
+// two auxiliary losses, over all T tokens as the batch.  bf16: the router kernels themselves leave, per block of 16
+// tokens, the slots on every expert and the sums of the routing probabilities (the logits, the softmax and the
+// selected set are in their registers anyway), and one final workgroup adds the blocks up in order
+// (route_stats_final_kernel).  fp32: logits to scratch (route_f32_kernel), per-block sums (route_stats_kernel), the
+// same final workgroup.  Every floating-point sum runs in a fixed order.
 // ---------------------------------------------------------------------------------------------
 constexpr int kStatsTokens = 64;  // tokens per workgroup of route_stats_kernel: four batches of four per wave
 
@@ -526,8 +625,10 @@ __global__ __launch_bounds__(kRouteThreads) void route_stats_kernel(const float 
     }
 }
 
+// f_part: [nblocks][NE] int32 counts, or NULL: then cnt8[e][cnt_ld] holds them as bytes
 __global__ __launch_bounds__(kRouteThreads) void route_stats_final_kernel(const float *__restrict__ p_part,
-                                                                          const int32_t *__restrict__ f_part, int nblocks,
+                                                                          const int32_t *__restrict__ f_part,
+                                                                          const uint8_t *__restrict__ cnt8, int cnt_ld, int nblocks,
                                                                           int T, int N, int NE, int K, float alpha, float w,
                                                                           float *__restrict__ f, float *__restrict__ P,
                                                                           float *__restrict__ summary)
@@ -537,7 +638,10 @@ __global__ __launch_bounds__(kRouteThreads) void route_stats_final_kernel(const 
     if (e < NE) {
         float ps = 0.f;
         long long fs = 0;
-        for (int b = 0; b < nblocks; ++b) { ps += p_part[(size_t)b * NE + e]; fs += f_part[(size_t)b * NE + e]; }
+        for (int b = 0; b < nblocks; ++b) {
+            ps += p_part[(size_t)b * NE + e];
+            fs += f_part ? f_part[(size_t)b * NE + e] : (int)cnt8[(size_t)e * cnt_ld + b];
+        }
         s_P[e] = ps / (float)T;
         s_f[e] = (float)((double)fs / (double)T);
         f[e] = s_f[e];
@@ -567,39 +671,37 @@ static size_t stats_logits_bytes(const zeda_layer_desc *d)
 }
 size_t routing_stats_ws_bytes(const zeda_layer_desc *d)
 {
-    const size_t nblk = (size_t)ceil_div(d->T, kStatsTokens), NE = (size_t)(d->N + d->Z);
+    const size_t NE = (size_t)(d->N + d->Z);
+    if (d->dtype == ZEDA_BF16)  // split-k scratch of the router, per-block counts, per-block probability sums
+        return align_up(route_ws_bytes(d), 256) + route_counts_bytes(d) + align_up((size_t)ceil_div(d->T, 16) * NE * 4, 256);
+    const size_t nblk = (size_t)ceil_div(d->T, kStatsTokens);
     return stats_logits_bytes(d) + align_up(nblk * NE * 4, 256) * 2;
 }
 
 int launch_routing_stats(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, float alpha, float w,
                          float *f, float *P, float *summary, void *ws, hipStream_t s)
 {
-    const int NE = d->N + d->Z, NB = ceil_div(NE, 32), LDg = NB * 32;
+    const int NE = d->N + d->Z;
+    if (d->dtype == ZEDA_BF16) {
+        float *partial = route_ws_bytes(d) ? (float *)ws : nullptr;
+        uint8_t *cnt8 = (uint8_t *)ws + align_up(route_ws_bytes(d), 256);
+        float *p_part = (float *)(cnt8 + route_counts_bytes(d));
+        const RouteExtras ex = {cnt8, route_counts_ld(d), p_part};
+        const int rc = launch_route_bf16_any(d, x, wr, bias, nullptr, nullptr, partial, ex, s);
+        if (rc != ZEDA_OK) return rc;
+        route_stats_final_kernel<<<1, kRouteThreads, 0, s>>>(p_part, nullptr, cnt8, ex.cnt_ld, ceil_div(d->T, 16), d->T, d->N, NE,
+                                                             d->K, alpha, w, f, P, summary);
+        return last_launch_status();
+    }
+    const int NB = ceil_div(NE, 32), LDg = NB * 32;
     const int Tpad = ceil_div(d->T, kRouteTokens) * kRouteTokens, nblk = ceil_div(d->T, kStatsTokens);
     float *logits = (float *)ws;
     float *p_part = (float *)((char *)ws + stats_logits_bytes(d));
     int32_t *f_part = (int32_t *)((char *)p_part + align_up((size_t)nblk * NE * 4, 256));
-    int nsplit = 1;
-    if (d->dtype == ZEDA_BF16) {
-        nsplit = route_ksplit(d);
-        int rc;
-        switch (NB) {
-            case 1: rc = launch_route_bf16<1>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 2: rc = launch_route_bf16<2>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 3: rc = launch_route_bf16<3>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 4: rc = launch_route_bf16<4>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 5: rc = launch_route_bf16<5>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 6: rc = launch_route_bf16<6>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            case 7: rc = launch_route_bf16<7>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-            default: rc = launch_route_bf16<8>(d, x, wr, bias, nullptr, nullptr, logits, s, true); break;
-        }
-        if (rc != ZEDA_OK) return rc;
-    } else {
-        route_f32_kernel<<<ceil_div(d->T, kRouteF32Tokens), kRouteThreads, 0, s>>>(
-            (const float *)x, (const float *)wr, bias, d->T, d->H, d->N, NE, d->K, d->gate_norm, nullptr, nullptr, logits, LDg);
-    }
+    route_f32_kernel<<<ceil_div(d->T, kRouteF32Tokens), kRouteThreads, 0, s>>>(
+        (const float *)x, (const float *)wr, bias, d->T, d->H, d->N, NE, d->K, d->gate_norm, nullptr, nullptr, logits, LDg);
     if (hipGetLastError() != hipSuccess) return ZEDA_EHIP;
-#define ZEDA_STATS(NC) route_stats_kernel<NC><<<nblk, kRouteThreads, 0, s>>>(logits, nsplit, Tpad, LDg, bias, d->T, NE, d->K, p_part, f_part)
+#define ZEDA_STATS(NC) route_stats_kernel<NC><<<nblk, kRouteThreads, 0, s>>>(logits, 1, Tpad, LDg, bias, d->T, NE, d->K, p_part, f_part)
     switch (ceil_div(NE, 16)) {
         case 1: ZEDA_STATS(1); break;   case 2: ZEDA_STATS(2); break;   case 3: ZEDA_STATS(3); break;
         case 4: ZEDA_STATS(4); break;   case 5: ZEDA_STATS(5); break;   case 6: ZEDA_STATS(6); break;
@@ -610,30 +712,22 @@ int launch_routing_stats(const zeda_layer_desc *d, const void *x, const void *wr
     }
 #undef ZEDA_STATS
     if (hipGetLastError() != hipSuccess) return ZEDA_EHIP;
-    route_stats_final_kernel<<<1, kRouteThreads, 0, s>>>(p_part, f_part, nblk, d->T, d->N, NE, d->K, alpha, w, f, P, summary);
+    route_stats_final_kernel<<<1, kRouteThreads, 0, s>>>(p_part, f_part, nullptr, 0, nblk, d->T, d->N, NE, d->K, alpha, w, f, P,
+                                                         summary);
     return last_launch_status();
 }
 
 int launch_route(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,
-                 float *gates, float *partial, hipStream_t s)
+                 float *gates, float *partial, uint8_t *cnt8, hipStream_t s)
 {
     const int NE = d->N + d->Z;
     if (d->dtype == ZEDA_BF16) {
-        switch (ceil_div(NE, 32)) {
-            case 1: return launch_route_bf16<1>(d, x, wr, bias, ids, gates, partial, s);
-            case 2: return launch_route_bf16<2>(d, x, wr, bias, ids, gates, partial, s);
-            case 3: return launch_route_bf16<3>(d, x, wr, bias, ids, gates, partial, s);
-            case 4: return launch_route_bf16<4>(d, x, wr, bias, ids, gates, partial, s);
-            case 5: return launch_route_bf16<5>(d, x, wr, bias, ids, gates, partial, s);
-            case 6: return launch_route_bf16<6>(d, x, wr, bias, ids, gates, partial, s);
-            case 7: return launch_route_bf16<7>(d, x, wr, bias, ids, gates, partial, s);
-            default: return launch_route_bf16<8>(d, x, wr, bias, ids, gates, partial, s);
-        }
-    } else {
-        dim3 grid(ceil_div(d->T, kRouteF32Tokens));
-        route_f32_kernel<<<grid, kRouteThreads, 0, s>>>((const float *)x, (const float *)wr, bias, d->T, d->H, d->N, NE,
-                                                        d->K, d->gate_norm, ids, gates, nullptr, 0);
+        const RouteExtras ex = {cnt8, cnt8 ? route_counts_ld(d) : 0, nullptr};
+        return launch_route_bf16_any(d, x, wr, bias, ids, gates, partial, ex, s);
     }
+    dim3 grid(ceil_div(d->T, kRouteF32Tokens));
+    route_f32_kernel<<<grid, kRouteThreads, 0, s>>>((const float *)x, (const float *)wr, bias, d->T, d->H, d->N, NE, d->K,
+                                                    d->gate_norm, ids, gates, nullptr, 0);
     return last_launch_status();
 }
 
