@@ -53,8 +53,13 @@ def test_workspace_sizes():
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     # fp32 doubles the float buffers; Z = 0 and T = 0 are valid layers
     assert zeda.workspace_bytes(_desc(dtype="f32")) > total
-    # Z only changes the router's scratch (one logit table row per token and split)
-    assert total - zeda.route_workspace_bytes(d) == zeda.workspace_bytes(_desc(Z=0)) - zeda.route_workspace_bytes(_desc(Z=0))
+    # Z only changes the router's scratch (one logit table row per token and split) and the dispatch region, which
+    # also holds the router's per-block counts of every expert
+    d0 = _desc(Z=0)
+    L0 = zeda.workspace_layout(d0)
+    assert (total - zeda.route_workspace_bytes(d) - (L.act - L.dispatch_ws)
+            == zeda.workspace_bytes(d0) - zeda.route_workspace_bytes(d0) - (L0.act - L0.dispatch_ws))
+    assert L.act - L.dispatch_ws >= (128 + 32) * (4096 // 16)
     assert zeda.workspace_bytes(_desc(T=0)) > 0
 
 
