@@ -27,11 +27,18 @@ from paper_2605_18643_amd import synth, zeda  # noqa: E402
 METRIC = "MoE-layer tokens/s (Qwen3-30B-A3B shape, ~50% zero slots) + MFMA util %"
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
-# HBM bytes per launch of the gate/up kernel, from the rocprofv3 counter runs summarised in
-# profiles/ffn_kernels_c2_qwen_prefill_hbm_traffic.txt (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB, both scales read
-# off a plain copy kernel in the same runs).  Counters cannot be read from inside this process, so the figure is
-# only reported for the workload and weight layout it was measured on.
-MEASURED_GATEUP_TRAFFIC_BYTES = {("c2_qwen_prefill", "tiled"): 897.6e6}
+# Counters cannot be read from inside this process.  These are RECORDED values of earlier rocprofv3 --pmc runs of this
+# same program (the summaries and their command lines are under profiles/); they are reported, labelled as recorded,
+# only for the workload and weight layout they were measured on, and are re-measured whenever the GEMM kernel changes.
+#   traffic: HBM bytes per launch of the gate/up kernel (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB, both scales read off
+#   a plain copy kernel in the same runs); mfma_busy_pct: SQ_VALU_MFMA_BUSY_CYCLES / (1024 SIMDs x cycles of the launch)
+RECORDED_COUNTERS = {
+    ("c2_qwen_prefill", "tiled"): {"traffic": 897.6e6, "traffic_source": "profiles/ffn_kernels_c2_qwen_prefill_hbm_traffic.txt",
+                                   "mfma_busy_pct": {"gateup": 31.1, "down": 25.8},
+                                   "mfma_busy_source": "profiles/ffn_kernels_c2_qwen_prefill_mfma_lds_counters.txt"},
+    ("c4_hetero_prefill", "tiled"): {"mfma_busy_pct": {"gateup": 48.6, "down": 38.6},
+                                     "mfma_busy_source": "profiles/ffn_kernels_c4_hetero_prefill_mfma_lds_counters.txt"},
+}
 CPU_BASELINE_SECONDS = 12.0      # the oracle keeps making passes over its token sample until this much time has gone by
 
 
@@ -198,6 +205,8 @@ def main() -> int:
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters; outside the timed region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-z0", action="store_true")
+    ap.add_argument("--no-sustained", action="store_true",
+                    help="skip the long back-to-back run that a short timed region (--steps < 500) is followed by")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short legs of configurations 3, 4 and 5 that the default run adds after the headline")
     ap.add_argument("--library-gemm", action="store_true",
@@ -252,6 +261,7 @@ def main() -> int:
     dn_flops = 2.0 * w.H * w.I * R
     gu_s, dn_s = stage["gateup"] * 1e-3, stage["down"] * 1e-3
     achieved_gbs = gu_bytes / gu_s / 1e9
+    recorded = RECORDED_COUNTERS.get((w.name, a.weights if w.dtype == "bf16" else "row_major"), {})
     # the binding roofline of the gate/up kernel on this workload: whichever of its two floors is the longer
     if gu_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) > gu_bytes / (HBM_PEAK_GBS * 1e9) and w.dtype == "bf16":
         achieved_tf = gu_flops / gu_s / 1e12
@@ -262,7 +272,7 @@ def main() -> int:
     else:
         roofline = {"kernel": "ffn_bf16_kernel<gate/up>", "bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
-                    "traffic": MEASURED_GATEUP_TRAFFIC_BYTES.get((w.name, a.weights if w.dtype == "bf16" else "row_major")),
+                    "traffic": recorded.get("traffic"), "traffic_source": recorded.get("traffic_source"),
                     "avg_launch_us": gu_s * 1e6, "algorithmic_bytes": gu_bytes}
     ffn_tflops = (gu_flops + dn_flops) / (gu_s + dn_s) / 1e12
     res = {
@@ -273,7 +283,10 @@ def main() -> int:
                    "real_slots": R, "r_ze": 1.0 - R / (w.T * w.K), "nonempty_experts": ne, "max_rows_per_expert": r["max_rows"],
                    "weight_layout": "tiled" if L.get("weight_layout") == zeda.WEIGHTS_TILED else "row_major"},
         "roofline": roofline,
+        # real-slot FLOPs of both GEMMs over their event-timed durations, against the 2.5 PFLOP/s peak (arithmetic) ...
         "mfma_util_pct": 100.0 * ffn_tflops / MFMA_BF16_PEAK_TFLOPS,
+        # ... and the MFMA pipes' busy share by counter, a recorded profile value (null where none was taken)
+        "mfma_busy_pct_recorded": recorded.get("mfma_busy_pct"), "mfma_busy_source": recorded.get("mfma_busy_source"),
         "expert_gemm": {"tflops": ffn_tflops, "peak_tflops": MFMA_BF16_PEAK_TFLOPS,
                         "gateup_tflops": gu_flops / gu_s / 1e12, "down_tflops": dn_flops / dn_s / 1e12,
                         "down_gbs": dn_bytes / dn_s / 1e9},
@@ -317,6 +330,14 @@ def main() -> int:
             lib[name] = {"us": dt * 1e6, "tflops": 2.0 * ne * m * kd * nd / dt / 1e12, "batch": ne, "rows": m}
             del A, B, C
         res["library_gemm"] = lib
+
+    if a.steps < 500 and not a.no_sustained:
+        # The timed region above is what was asked for.  A short region after idle sits in the clock transient of the
+        # first milliseconds of heavy work; the same step measured over a long back-to-back run is reported beside it.
+        rs = run_layer(w, L, 600, 150)
+        res["sustained"] = {"steps": 600, "warmup": 150, "ms_per_step": rs["wall_s"] / 600 * 1e3,
+                            "tokens_per_s": w.T * 600 / rs["wall_s"],
+                            "stage_us": {k: float(v) * 1e3 for k, v in zip(zeda.STAGES, rs["stage_ms"])}}
 
     if w.name == "c2_qwen_prefill" and a.tokens <= 0 and not a.no_other_configs:
         res["other_configs"] = other_config_legs(a.weights == "tiled")
