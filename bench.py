@@ -33,7 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 #   traffic: HBM bytes per launch of the gate/up kernel (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB, both scales read off
 #   a plain copy kernel in the same runs); mfma_busy_pct: SQ_VALU_MFMA_BUSY_CYCLES / (1024 SIMDs x cycles of the launch)
 RECORDED_COUNTERS = {
-    ("c2_qwen_prefill", "tiled"): {"traffic": 897.6e6, "traffic_source": "profiles/ffn_kernels_c2_qwen_prefill_hbm_traffic.txt",
+    ("c2_qwen_prefill", "tiled"): {"traffic": 898.3e6, "traffic_source": "profiles/ffn_kernels_c2_qwen_prefill_hbm_traffic.txt",
                                    "mfma_busy_pct": {"gateup": 31.1, "down": 25.8},
                                    "mfma_busy_source": "profiles/ffn_kernels_c2_qwen_prefill_mfma_lds_counters.txt"},
     ("c4_hetero_prefill", "tiled"): {"mfma_busy_pct": {"gateup": 48.6, "down": 38.6},
