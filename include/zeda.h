@@ -244,6 +244,15 @@ int zeda_moe_block_forward(const zeda_layer_desc *desc, const void *xn, void *x_
                            const void *gamma_next, float eps, void *xn_next, int32_t *num_real_out, void *ws,
                            size_t ws_bytes, void *stream);
 
+/* Measurement aid, not part of the layer: reads `bytes` bytes of device memory at `buf` once, every workgroup a
+ * contiguous 256 KiB run with 16-byte loads - the plainest streaming read there is.  Its rate on a buffer larger than
+ * the caches is what HBM delivers to a kernel that does nothing else on this machine, the yardstick beside which
+ * bench.py reports the rates of the HBM-bound expert GEMMs (the published 8 TB/s is not reached by any read
+ * pattern).  Nothing is written unless the XOR of all words read equals an arbitrary constant, in which case one
+ * word is stored to sink (device, 4 bytes; exists so that the loads cannot be dropped).  buf 16-byte aligned,
+ * bytes a multiple of 16.  ZEDA_EINVAL on NULL / unaligned arguments; bytes == 0 launches nothing. */
+int zeda_stream_read_probe(const void *buf, size_t bytes, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -132,6 +132,32 @@ static int forward_impl(const zeda_layer_desc *desc, const void *x, const void *
     return rc;
 }
 
+// Plain streaming read (zeda_stream_read_probe): a workgroup reads one contiguous run of kProbeRun bytes, four
+// 16-byte loads per lane in flight.
+constexpr size_t kProbeRun = 256 * 1024;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *__restrict__ p, size_t n16, uint32_t *__restrict__ sink)
+{
+    constexpr size_t per_wg = kProbeRun / 16;
+    const size_t lo = (size_t)blockIdx.x * per_wg, hi = lo + per_wg < n16 ? lo + per_wg : n16;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    size_t i = lo + threadIdx.x;
+    for (; i + 768 < hi; i += 1024) {
+        const u32x4 a = p[i], b = p[i + 256], c = p[i + 512], d = p[i + 768];
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < hi; i += 256) acc ^= p[i];
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x5eda5edau && (acc[0] + acc[1]) == 0x0badcafeu) *sink = acc[2];
+}
+
+static int launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hipStream_t s)
+{
+    const size_t n16 = bytes / 16, grid = (bytes + kProbeRun - 1) / kProbeRun;
+    if (grid > 0x7fffffffu) return ZEDA_EUNSUPPORTED;
+    stream_read_kernel<<<(unsigned)grid, 256, 0, s>>>((const u32x4 *)buf, n16, sink);
+    return last_launch_status();
+}
+
 }  // namespace zeda
 
 using namespace zeda;
@@ -343,6 +369,13 @@ int zeda_pack_expert_weights(const zeda_layer_desc *desc, const void *w_gate, co
         if (rc != ZEDA_OK) return rc;
     }
     return ZEDA_OK;
+}
+
+int zeda_stream_read_probe(const void *buf, size_t bytes, void *sink, void *stream)
+{
+    if (!buf || !sink || !aligned16(buf) || (bytes & 15u) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return ZEDA_EINVAL;
+    if (bytes == 0) return ZEDA_OK;
+    return launch_stream_read(buf, bytes, (uint32_t *)sink, (hipStream_t)stream);
 }
 
 }  // extern "C"

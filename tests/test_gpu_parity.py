@@ -120,3 +120,19 @@ def test_empty_batch_is_a_no_op_on_every_entry_point():
     assert (guard.float() == 7.0).all() and (ids == -9).all() and (gates == -9.0).all()
     assert not off.cpu().numpy().any() and int(nr.item()) == 0 and (ss == -5).all() and (s2r == -5).all()
     assert int(nreal.item()) == 0  # the whole-layer call reports R = 0
+
+
+def test_stream_read_probe_reads_and_rejects_bad_arguments():
+    """The measurement aid: runs over a buffer with a ragged tail (not a multiple of a workgroup's run), writes
+    nothing, and turns unaligned arguments into ZEDA_EINVAL."""
+    buf = torch.arange((3 * 256 * 1024 + 4096) // 4, dtype=torch.int32, device="cuda")
+    sink = torch.full((1,), 7, dtype=torch.int32, device="cuda")
+    zeda.zeda_stream_read_probe(buf, sink)
+    zeda.zeda_stream_read_probe(buf[:4], sink)  # 16 bytes
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 7
+    with pytest.raises(zeda.ZedaError) as e:
+        zeda.zeda_stream_read_probe(buf[1:5], sink)  # 4 bytes past a 16-byte boundary
+    assert e.value.status < 0
+    with pytest.raises(zeda.ZedaError):
+        zeda.zeda_stream_read_probe(buf[:5], sink)  # 20 bytes
