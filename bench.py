@@ -42,14 +42,27 @@ RECORDED_COUNTERS = {
 CPU_BASELINE_SECONDS = 12.0      # the oracle keeps making passes over its token sample until this much time has gone by
 
 
-def run_layer(w: synth.Workload, L, steps: int, warmup: int):
+def run_layer(w: synth.Workload, L, steps: int, warmup: int, lead_in=None):
     """Times `steps` forward passes (whole-path wall time) and, in a second loop of the same length,
-    each stage with HIP events recorded between the kernels on the launch stream."""
+    each stage with HIP events recorded between the kernels on the launch stream.
+    lead_in = (steps, warmup): a long back-to-back run of the same step, timed the same way, directly in front of the
+    warm-up (nothing but one synchronise in between), so that the region asked for starts on a chip at its working
+    clocks; its wall time per step is returned as lead_in_ms."""
     d = zeda.make_desc(w.T, w.H, w.I, w.N, w.Z, w.K, w.dtype, weight_layout=L.get("weight_layout", zeda.WEIGHTS_ROW_MAJOR))
     ws = torch.empty(zeda.workspace_bytes(d), dtype=torch.uint8, device="cuda")
     out = torch.empty((w.T, w.H), dtype=w.torch_dtype, device="cuda")
     nreal = torch.zeros(1, dtype=torch.int32, device="cuda")
     args = (d, L["x"], L["w_router"], L["router_bias"], L["w_gate"], L["w_up"], L["w_down"], out, nreal, ws)
+    lead_in_ms = None
+    if lead_in:
+        for _ in range(lead_in[1]):
+            zeda.zeda_moe_forward(*args)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(lead_in[0]):
+            zeda.zeda_moe_forward(*args)
+        torch.cuda.synchronize()
+        lead_in_ms = (time.perf_counter() - t0) / lead_in[0] * 1e3
     for _ in range(warmup):
         zeda.zeda_moe_forward(*args)
     torch.cuda.synchronize()
@@ -77,7 +90,7 @@ def run_layer(w: synth.Workload, L, steps: int, warmup: int):
     off = v["expert_offsets"].cpu().numpy()
     R = int(nreal.item())
     return {"wall_s": wall, "stage_ms": stage_ms, "R": R, "nonempty": int((np.diff(off) > 0).sum()),
-            "max_rows": int(np.diff(off).max()), "out": out}
+            "max_rows": int(np.diff(off).max()), "out": out, "lead_in_ms": lead_in_ms}
 
 
 def time_stack(layers: int, steps: int, warmup: int, tiled: bool):
@@ -251,20 +264,21 @@ def main() -> int:
         L = pack_layer(w, L)
     torch.cuda.synchronize()
     # A short timed region right after idle sits in the clock transient of the chip's first milliseconds of heavy
-    # work.  So a short run (--steps < 500) first takes the same region cold (reported as `cold_start`), then a long
-    # back-to-back run (`sustained`), and only then - the chip now at its working clocks - the warm-up and the timed
-    # steps that were asked for, which are what `value` reports.  --cold-start keeps the old order (value = cold).
+    # work (a gap of a millisecond is enough to fall back into it).  So a short run (--steps < 500) first takes the
+    # same region cold (reported as `cold_start`), then a long back-to-back run (`sustained`) and, with nothing but a
+    # synchronise in between - the chip now at its working clocks - the warm-up and the timed steps that were asked
+    # for, which are what `value` reports.  --cold-start keeps the old order (value = cold).
     pre = {}
-    if a.steps < 500 and not a.no_sustained and not a.cold_start:
+    warm_order = a.steps < 500 and not a.no_sustained and not a.cold_start
+    if warm_order:
         rc = run_layer(w, L, a.steps, a.warmup)
         pre["cold_start"] = {"steps": a.steps, "warmup": a.warmup, "ms_per_step": rc["wall_s"] / a.steps * 1e3,
                              "tokens_per_s": w.T * a.steps / rc["wall_s"],
                              "stage_us": {k: float(v) * 1e3 for k, v in zip(zeda.STAGES, rc["stage_ms"])}}
-        rs = run_layer(w, L, 600, 150)
-        pre["sustained"] = {"steps": 600, "warmup": 150, "ms_per_step": rs["wall_s"] / 600 * 1e3,
-                            "tokens_per_s": w.T * 600 / rs["wall_s"],
-                            "stage_us": {k: float(v) * 1e3 for k, v in zip(zeda.STAGES, rs["stage_ms"])}}
-    r = run_layer(w, L, a.steps, a.warmup)
+    r = run_layer(w, L, a.steps, a.warmup, lead_in=(600, 150) if warm_order else None)
+    if warm_order:
+        pre["sustained"] = {"steps": 600, "warmup": 150, "ms_per_step": r["lead_in_ms"],
+                            "tokens_per_s": w.T / (r["lead_in_ms"] * 1e-3)}
     ms = r["wall_s"] / a.steps * 1e3
     tokens_per_s = w.T * a.steps / r["wall_s"]
 
@@ -346,7 +360,7 @@ def main() -> int:
     if not a.no_z0 and w.Z > 0:
         # the same kernels on the static layer: no zero experts, top-K over the N normal experts only
         w0, L0 = static_twin(w, L)
-        r0 = run_layer(w0, L0, a.steps, a.warmup)
+        r0 = run_layer(w0, L0, a.steps, a.warmup, lead_in=(300, 100) if warm_order else None)  # (the same way)
         res["z0"] = {"ms_per_step": r0["wall_s"] / a.steps * 1e3, "speedup_vs_z0": r0["wall_s"] / r["wall_s"],
                      "real_slots": r0["R"], "expert_flop_reduction": 1.0 - R / max(1, r0["R"]),
                      "stage_us": {k: float(v) * 1e3 for k, v in zip(zeda.STAGES, r0["stage_ms"])}}
