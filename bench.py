@@ -356,6 +356,19 @@ def main() -> int:
                                           "delivers on this machine to a kernel that does nothing else"}
         if roofline["bound"] == "hbm":
             roofline["frac_of_stream_read"] = achieved_gbs / stream_gbs
+        # Yardstick for the compute-heavy kernels: the library's register-only MFMA loop (no memory traffic), two
+        # workgroups per CU, long enough to reach the clock the chip holds under it.
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        msink = torch.empty(2 * cus * 256, dtype=torch.float32, device="cuda")
+        zeda.zeda_mfma_probe(2 * cus, 20000, msink)
+        e0.record()
+        flops = sum(zeda.zeda_mfma_probe(2 * cus, 20000, msink) for _ in range(4))
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_tf = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        res["mfma_probe"] = {"tflops": mfma_tf, "frac_of_peak": mfma_tf / MFMA_BF16_PEAK_TFLOPS,
+                             "note": "zeda_mfma_probe: independent 32x32x16 bf16 MFMAs on register operands, nothing else; "
+                                     "what the matrix units deliver on this machine without any data movement"}
 
     if not a.no_z0 and w.Z > 0:
         # the same kernels on the static layer: no zero experts, top-K over the N normal experts only
@@ -395,6 +408,9 @@ def main() -> int:
 
     if w.name == "c2_qwen_prefill" and a.tokens <= 0 and not a.no_other_configs:
         res["other_configs"] = other_config_legs(a.weights == "tiled")
+        if "mfma_probe" in res:
+            c4 = res["other_configs"]["c4_hetero_prefill"]
+            c4["gateup_frac_of_mfma_probe"] = c4["gateup_tflops"] / res["mfma_probe"]["tflops"]
 
     if not a.no_cpu_baseline:
         from oracle import harness, zeda_oracle as orc  # CPU-baseline leg only

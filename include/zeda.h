@@ -253,6 +253,14 @@ int zeda_moe_block_forward(const zeda_layer_desc *desc, const void *xn, void *x_
  * bytes a multiple of 16.  ZEDA_EINVAL on NULL / unaligned arguments; bytes == 0 launches nothing. */
 int zeda_stream_read_probe(const void *buf, size_t bytes, void *sink, void *stream);
 
+/* Measurement aid, not part of the layer: `workgroups` workgroups of four waves each issue iters * 8 independent
+ * 32x32x16 bf16 MFMAs (fp32 accumulators, operands held in registers, no memory traffic at all): the rate of
+ * 2 * 32*32*16 * 8 * iters * 4 * workgroups FLOPs over the launch is what the matrix units deliver on this machine when
+ * nothing else competes for power or issue slots - the yardstick beside which bench.py reports the compute-heavy
+ * expert GEMMs.  The accumulators are summed into sink[workgroup * 256 + thread] (device, workgroups * 256 floats) so
+ * that the work cannot be dropped.  ZEDA_EINVAL on NULL / unaligned sink, iters < 1, workgroups < 1. */
+int zeda_mfma_probe(int workgroups, int iters, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

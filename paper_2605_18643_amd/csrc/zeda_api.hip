@@ -158,6 +158,33 @@ static int launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hip
     return last_launch_status();
 }
 
+// zeda_mfma_probe: eight independent accumulator blocks per wave, the same two operand fragments every time
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ sink, int iters)
+{
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t h = (threadIdx.x * 8u + i) * 2654435761u;  // fixed pseudo-random operands in (-1, 1)
+        a[i] = (bf16_t)(((h >> 8) & 0xffff) / 32768.0f - 1.0f);
+        b[i] = (bf16_t)(((h >> 16) & 0xffff) / 32768.0f - 1.0f);
+    }
+    f32x16 acc[8];
+#pragma unroll
+    for (int n = 0; n < 8; ++n)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int n = 0; n < 8; ++n)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[n][v];
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 }  // namespace zeda
 
 using namespace zeda;
@@ -376,6 +403,13 @@ int zeda_stream_read_probe(const void *buf, size_t bytes, void *sink, void *stre
     if (!buf || !sink || !aligned16(buf) || (bytes & 15u) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return ZEDA_EINVAL;
     if (bytes == 0) return ZEDA_OK;
     return launch_stream_read(buf, bytes, (uint32_t *)sink, (hipStream_t)stream);
+}
+
+int zeda_mfma_probe(int workgroups, int iters, float *sink, void *stream)
+{
+    if (!sink || (reinterpret_cast<uintptr_t>(sink) & 3u) || iters < 1 || workgroups < 1) return ZEDA_EINVAL;
+    mfma_probe_kernel<<<(unsigned)workgroups, 256, 0, (hipStream_t)stream>>>(sink, iters);
+    return last_launch_status();
 }
 
 }  // extern "C"

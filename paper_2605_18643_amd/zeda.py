@@ -27,7 +27,7 @@ EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_route_workspace_b
            "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events", "zeda_moe_block_forward",
            "zeda_rmsnorm",
            "zeda_residual_add", "zeda_pack_expert_weights", "zeda_routing_stats_workspace_bytes", "zeda_routing_stats",
-           "zeda_init_zero_expert_rows", "zeda_stream_read_probe")
+           "zeda_init_zero_expert_rows", "zeda_stream_read_probe", "zeda_mfma_probe")
 
 
 class LayerDesc(ctypes.Structure):
@@ -93,6 +93,8 @@ def lib() -> ctypes.CDLL:
         L.zeda_routing_stats.argtypes = [dp, vp, vp, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp, sz, vp]
         L.zeda_init_zero_expert_rows.restype = i32
         L.zeda_init_zero_expert_rows.argtypes = [dp, vp, vp, vp, vp]
+        L.zeda_mfma_probe.restype = i32
+        L.zeda_mfma_probe.argtypes = [i32, i32, vp, vp]
         L.zeda_stream_read_probe.restype = i32
         L.zeda_stream_read_probe.argtypes = [vp, sz, vp, vp]
         L.zeda_pack_expert_weights.restype = i32
@@ -227,6 +229,14 @@ def zeda_stream_read_probe(buf: torch.Tensor, sink: torch.Tensor, stream=None) -
            "zeda_stream_read_probe")
 
 
+def zeda_mfma_probe(workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Measurement aid: launches the register-only MFMA loop; returns the FLOPs of the launch.  sink: fp32, at least
+    workgroups * 256 elements."""
+    assert sink.dtype == torch.float32 and sink.numel() >= workgroups * 256
+    _check(lib().zeda_mfma_probe(int(workgroups), int(iters), _ptr(sink), _stream(stream)), "zeda_mfma_probe")
+    return 2.0 * 32 * 32 * 16 * 8 * iters * 4 * workgroups
+
+
 def zeda_residual_add(x, y, stream=None) -> None:
     T, H = x.shape
     _check(lib().zeda_residual_add(T, H, _dtype_code(x), _ptr(x), _ptr(y), _stream(stream)), "zeda_residual_add")
@@ -251,7 +261,7 @@ def zeda_init_zero_expert_rows(desc, w_router, normals, stream=None):
     """Fills rows N.. of w_router in place (see include/zeda.h); returns the device tensor {mean, variance}."""
     stats = torch.empty(2, dtype=torch.float32, device=w_router.device)
     _check(lib().zeda_init_zero_expert_rows(ctypes.byref(desc), _ptr(w_router), _ptr(normals), _ptr(stats), _stream(stream)),
-           "zeda_init_zero_expert_rows", "zeda_stream_read_probe")
+           "zeda_init_zero_expert_rows")
     return stats
 
 

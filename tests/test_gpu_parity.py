@@ -136,3 +136,15 @@ def test_stream_read_probe_reads_and_rejects_bad_arguments():
     assert e.value.status < 0
     with pytest.raises(zeda.ZedaError):
         zeda.zeda_stream_read_probe(buf[:5], sink)  # 20 bytes
+
+
+def test_mfma_probe_runs_and_rejects_bad_arguments():
+    sink = torch.zeros(4 * 256, dtype=torch.float32, device="cuda")
+    flops = zeda.zeda_mfma_probe(4, 3, sink)
+    torch.cuda.synchronize()
+    assert flops == 2.0 * 32 * 32 * 16 * 8 * 3 * 4 * 4
+    assert torch.isfinite(sink).all() and float(sink.abs().sum()) > 0.0
+    for wg, it in ((0, 3), (4, 0)):
+        with pytest.raises(zeda.ZedaError):
+            zeda.lib()  # (argument checks run on the host)
+            zeda._check(zeda.lib().zeda_mfma_probe(wg, it, zeda._ptr(sink), None), "zeda_mfma_probe")
