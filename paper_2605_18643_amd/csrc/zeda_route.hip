@@ -481,7 +481,9 @@ static int launch_route_bf16_wide(const zeda_layer_desc *d, const void *x, const
     return last_launch_status();
 }
 
-constexpr int kRouteWideTokens = 12288;  // from here on the 64-token blocks alone give every CU a workgroup or nearly
+// More than 256 blocks of 32 tokens: a second round of 32-token workgroups would start behind the first (8500 tokens:
+// 38 us); 64-token blocks run in one round and read the router rows half as often (33 us from 8193 to 16384 tokens).
+constexpr int kRouteWideTokens = 8193;
 
 template <int NB>
 static int launch_route_bf16(const zeda_layer_desc *d, const void *x, const void *wr, const float *bias, int32_t *ids,

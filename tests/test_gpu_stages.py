@@ -66,9 +66,10 @@ def test_route_with_scratch_splits_the_hidden_dimension(T, H):
         np.testing.assert_allclose(gates.cpu().numpy().astype(np.float64), rg, rtol=2e-5, atol=1e-7)
 
 
-@pytest.mark.parametrize("T, N, Z", [(12288, 128, 32), (12301, 30, 10), (13000, 150, 42), (12500, 200, 56)])
+@pytest.mark.parametrize("T, N, Z", [(8192, 128, 32), (8193, 128, 32), (9001, 70, 26), (12288, 128, 32), (12301, 30, 10),
+                                     (13000, 150, 42), (12500, 200, 56)])
 def test_route_of_many_tokens(T, N, Z):
-    # from 12288 tokens on the bf16 router gives a workgroup 64 tokens instead of 32 (routers of up to 192
+    # above 8192 tokens the bf16 router gives a workgroup 64 tokens instead of 32 (routers of up to 192
     # experts; wider ones keep the 32-token blocks): exact ids and gates against the oracle, ragged last block
     w = synth.Workload("route_wide", T=T, H=256, I=64, N=N, Z=Z, K=6, dtype="bf16", seed=53, recipe="zero_bias",
                        wr_std=0.08, zero_bias=0.3)
