@@ -425,14 +425,15 @@ __global__ __launch_bounds__(kRouteThreads) void route_f32_kernel(const float *_
     select_block<kMaxExperts / 16, 1, 4>(lg, LD, 0, 1, bias, kRouteF32Tokens, t0, T, NE, N, K, gate_norm, ids, gates);
 }
 
-// How many workgroups share a token block (bf16 with scratch): enough to fill the device when there are few
-// token blocks, never more than eight, and the hidden dimension must split into whole 64-wide chunks.
+// How many workgroups share a token block (bf16 with scratch): as many as still run in one round of workgroups
+// (one per CU; a round and a half costs as much as two), never more than eight, and the hidden dimension must split
+// into whole 64-wide chunks.
 int route_ksplit(const zeda_layer_desc *d)
 {
     if (d->dtype != ZEDA_BF16) return 1;
     const int blocks = ceil_div(d->T, kRouteTokens), chunks = d->H / 64;
     int c = 1;
-    while (c < 8 && blocks * c < 256 && chunks % (2 * c) == 0) c *= 2;
+    while (c < 8 && blocks * 2 * c <= 256 && chunks % (2 * c) == 0) c *= 2;
     return c;
 }
 
