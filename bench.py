@@ -113,6 +113,17 @@ def time_stack(layers: int, steps: int, warmup: int, tiled: bool):
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / steps
         res[name] = {"ms_per_pass": dt * 1e3, "real_slots": int(stack.num_real.sum().item())}
+        if name == "z32":
+            # one more pass, untimed: per token, the share of its slots over all layers that landed on zero experts
+            # (the token-level r_ZE of Section 4.1; the per-layer one is 1 - real slots / slots of that layer)
+            tz = torch.zeros(w.T, dtype=torch.int32, device="cuda")
+            stack.forward(x.copy_(x0), token_zero=tz)
+            torch.cuda.synchronize()
+            share = tz.float().cpu().numpy() / (layers * w.K)
+            per_layer = 1.0 - stack.num_real.float().cpu().numpy() / (w.T * w.K)
+            res[name]["token_r_ze"] = {"mean": float(share.mean()), "min": float(share.min()), "max": float(share.max()),
+                                       "p10": float(np.percentile(share, 10)), "p90": float(np.percentile(share, 90))}
+            res[name]["layer_r_ze"] = {"min": float(per_layer.min()), "max": float(per_layer.max())}
     del st
     torch.cuda.empty_cache()
     return w, {"layers": layers, "T": w.T, "steps": steps, "warmup": warmup,

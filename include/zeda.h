@@ -212,6 +212,16 @@ typedef struct {
 } zeda_ws_layout;
 int zeda_workspace_layout(const zeda_layer_desc *desc, zeda_ws_layout *layout /* host */);
 
+/* Token-level zero-expert usage (Section 4.1, "Zero Expert Activation Dynamics": different tokens have different
+ * r_ZE): zero_slots[t] = number of the K slots of token t that landed on a zero expert (topk_ids[t,j] >= N), so a
+ * token's r_ZE in this layer is zero_slots[t] / K.  accumulate != 0 adds the counts to what zero_slots already
+ * holds instead of overwriting it: summed over the L layers of a model, zero_slots[t] / (L*K) is the token's r_ZE
+ * over the model.  topk_ids: [T,K] device, as written by zeda_route (the forward workspace holds it at
+ * zeda_ws_layout.topk_ids).  zero_slots: int32[T] device.  T = 0 is a no-op.  ZEDA_EINVAL on NULL / unaligned
+ * pointers. */
+int zeda_token_zero_slots(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t *zero_slots, int accumulate,
+                          void *stream);
+
 /* Router rows of the zero experts (Section 2.1, "router initialization"; a model-surgery step, not on the hot
  * path).  w_router[N+Z, H]: rows 0..N-1 (the post-trained router) are read and kept; rows N..N+Z-1 are written
  * as mean + std * normals[z, h], mean and (population) variance taken over the N*H original parameters.

@@ -172,6 +172,17 @@ def routing_stats(x, w_router, router_bias, N: int, Z: int, K: int, alpha: float
     return {"f": f, "P": P, **{k: float(v) for k, v in zip(keys, summ)}}
 
 
+def token_zero_slots(ids, N: int) -> np.ndarray:
+    """Token-level zero-expert usage (Section 4.1, "Zero Expert Activation Dynamics": tokens differ in their r_ZE): for
+    every token the number of its K selected slots that are zero experts (id >= N).  A token's r_ZE in one layer is
+    this count over K; over a model, the sum of the counts of its layers over layers * K."""
+    ids = np.asarray(ids)
+    out = np.zeros(ids.shape[0], dtype=np.int64)
+    for j in range(ids.shape[1]):
+        out += ids[:, j] >= N
+    return out
+
+
 def init_zero_rows(w_router_normal, normals):
     """Section 2.1, router initialisation: rows[Z,H] = mean + std * normals, (mean, variance) of the N*H originals."""
     lib = _load()

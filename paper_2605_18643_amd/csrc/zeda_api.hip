@@ -132,6 +132,17 @@ static int forward_impl(const zeda_layer_desc *desc, const void *x, const void *
     return rc;
 }
 
+// zeda_token_zero_slots: one thread per token walks its K ids
+__global__ __launch_bounds__(256) void token_zero_slots_kernel(const int32_t *__restrict__ ids, int T, int K, int N,
+                                                               int32_t *__restrict__ zero_slots, int accumulate)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= T) return;
+    int c = 0;
+    for (int j = 0; j < K; ++j) c += ids[(size_t)t * K + j] >= N;
+    zero_slots[t] = accumulate ? zero_slots[t] + c : c;
+}
+
 // Plain streaming read (zeda_stream_read_probe): a workgroup reads one contiguous run of kProbeRun bytes, four
 // 16-byte loads per lane in flight.
 constexpr size_t kProbeRun = 256 * 1024;
@@ -396,6 +407,19 @@ int zeda_pack_expert_weights(const zeda_layer_desc *desc, const void *w_gate, co
         if (rc != ZEDA_OK) return rc;
     }
     return ZEDA_OK;
+}
+
+int zeda_token_zero_slots(const zeda_layer_desc *desc, const int32_t *topk_ids, int32_t *zero_slots, int accumulate,
+                          void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != ZEDA_OK) return rc;
+    if (desc->T == 0) return ZEDA_OK;
+    if (!topk_ids || !zero_slots || (reinterpret_cast<uintptr_t>(topk_ids) & 3u) || (reinterpret_cast<uintptr_t>(zero_slots) & 3u))
+        return ZEDA_EINVAL;
+    token_zero_slots_kernel<<<ceil_div(desc->T, 256), 256, 0, (hipStream_t)stream>>>(topk_ids, desc->T, desc->K, desc->N,
+                                                                                    zero_slots, accumulate);
+    return last_launch_status();
 }
 
 int zeda_stream_read_probe(const void *buf, size_t bytes, void *sink, void *stream)

@@ -52,8 +52,11 @@ class MoeStack:
         twin.num_real = torch.zeros_like(self.num_real)
         return twin
 
-    def forward(self, x: torch.Tensor, hook=None, fused: Optional[bool] = None) -> torch.Tensor:
+    def forward(self, x: torch.Tensor, hook=None, fused: Optional[bool] = None,
+                token_zero: Optional[torch.Tensor] = None) -> torch.Tensor:
         """Runs the chain in place on x (the residual stream) and returns it.  The stream is never synchronised.
+        token_zero (int32[T], device): receives, per token, the number of its slots that landed on zero experts summed
+        over all layers (Section 4.1's token-level r_ZE is that over layers * K).
         fused (default: whenever no hook is given): one zeda_moe_block_forward per layer, whose combine stage adds
         into x and writes the next layer's normalised input; one RMSNorm kernel for the first layer only.
         hook(l, stack, x) is then called before layer l (self.xn is its input, x the stream so far) and once more
@@ -62,6 +65,7 @@ class MoeStack:
         before the residual add."""
         if fused is None:
             fused = hook is None
+        ids = zeda.ws_views(self.desc, self.ws)["topk_ids"] if token_zero is not None else None
         if fused:
             zeda.zeda_rmsnorm(x, None, EPS, self.xn)
             for l, p in enumerate(self.weights):
@@ -71,6 +75,8 @@ class MoeStack:
                 zeda.zeda_moe_block_forward(self.desc, self.xn, x, p["w_router"], p["router_bias"], p["w_gate"],
                                             p["w_up"], p["w_down"], None, EPS, None if last else self.xn,
                                             self.num_real[l: l + 1], self.ws)
+                if token_zero is not None:
+                    zeda.zeda_token_zero_slots(self.desc, ids, token_zero, accumulate=l > 0)
             if hook is not None:
                 hook(self.layers, self, x)
             return x
@@ -78,6 +84,8 @@ class MoeStack:
             zeda.zeda_rmsnorm(x, None, EPS, self.xn)
             zeda.zeda_moe_forward(self.desc, self.xn, p["w_router"], p["router_bias"], p["w_gate"], p["w_up"], p["w_down"],
                                   self.y, self.num_real[l: l + 1], self.ws)
+            if token_zero is not None:
+                zeda.zeda_token_zero_slots(self.desc, ids, token_zero, accumulate=l > 0)
             if hook is not None:
                 hook(l, self)
             zeda.zeda_residual_add(x, self.y)

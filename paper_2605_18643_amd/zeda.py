@@ -27,7 +27,7 @@ EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_route_workspace_b
            "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events", "zeda_moe_block_forward",
            "zeda_rmsnorm",
            "zeda_residual_add", "zeda_pack_expert_weights", "zeda_routing_stats_workspace_bytes", "zeda_routing_stats",
-           "zeda_init_zero_expert_rows", "zeda_stream_read_probe", "zeda_mfma_probe")
+           "zeda_init_zero_expert_rows", "zeda_stream_read_probe", "zeda_mfma_probe", "zeda_token_zero_slots")
 
 
 class LayerDesc(ctypes.Structure):
@@ -93,6 +93,8 @@ def lib() -> ctypes.CDLL:
         L.zeda_routing_stats.argtypes = [dp, vp, vp, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp, sz, vp]
         L.zeda_init_zero_expert_rows.restype = i32
         L.zeda_init_zero_expert_rows.argtypes = [dp, vp, vp, vp, vp]
+        L.zeda_token_zero_slots.restype = i32
+        L.zeda_token_zero_slots.argtypes = [dp, vp, vp, i32, vp]
         L.zeda_mfma_probe.restype = i32
         L.zeda_mfma_probe.argtypes = [i32, i32, vp, vp]
         L.zeda_stream_read_probe.restype = i32
@@ -227,6 +229,12 @@ def zeda_stream_read_probe(buf: torch.Tensor, sink: torch.Tensor, stream=None) -
     """Measurement aid: one plain streaming read of all bytes of `buf` (contiguous, a multiple of 16 bytes)."""
     _check(lib().zeda_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream(stream)),
            "zeda_stream_read_probe")
+
+
+def zeda_token_zero_slots(desc, topk_ids, zero_slots, accumulate: bool = False, stream=None) -> None:
+    """zero_slots[t] (int32[T], device) = or += the number of token t's K slots on zero experts (Section 4.1)."""
+    _check(lib().zeda_token_zero_slots(ctypes.byref(desc), _ptr(topk_ids), _ptr(zero_slots), int(bool(accumulate)),
+                                       _stream(stream)), "zeda_token_zero_slots")
 
 
 def zeda_mfma_probe(workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> float:

@@ -252,3 +252,31 @@ def test_stack_with_tiled_weights_matches_row_major_bit_for_bit():
         torch.cuda.synchronize()
     assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
     assert np.isfinite(outs[0].float().cpu().numpy()).all()
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_stack_token_level_zero_slots(fused):
+    # per token, the zero-expert slots summed over the layers (Section 4.1's token-level r_ZE times layers * K): every
+    # layer's share is checked against the oracle's count on the ids that layer's router wrote, and the total against
+    # the real-slot counts the layers report
+    w = synth.Workload("stack_tz", T=150, H=256, I=128, N=8, Z=4, K=3, dtype="bf16", seed=93, recipe="zero_bias",
+                       x_std=1.0, w_std=0.05, wr_std=0.05, zero_bias=0.3)
+    _say("stack, token-level zero slots, fused" if fused else "stack, token-level zero slots, three calls per layer", w)
+    st = MoeStack(w, layers=4)
+    per_layer = []
+
+    def hook(l, stack, *rest):
+        # fused: called before layer l, so the ids in the workspace are layer l-1's; unfused: after layer l
+        if fused and l == 0:
+            return
+        torch.cuda.synchronize()
+        per_layer.append(orc.token_zero_slots(zeda.ws_views(stack.desc, stack.ws)["topk_ids"].cpu().numpy(), w.N))
+
+    tz = torch.full((w.T,), 123, dtype=torch.int32, device="cuda")
+    st.forward(synth.draw_tokens(w, "cuda"), hook=hook, fused=fused, token_zero=tz)
+    torch.cuda.synchronize()
+    assert len(per_layer) == 4
+    got = tz.cpu().numpy()
+    assert np.array_equal(got, np.sum(per_layer, axis=0))
+    assert int(got.sum()) == 4 * w.T * w.K - int(st.num_real.sum().item())
+    assert got.min() >= 0 and got.max() <= 4 * w.K

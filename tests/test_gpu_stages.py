@@ -216,3 +216,30 @@ def test_dispatch_of_long_slot_lists(T, N, Z, K):
     assert np.array_equal(off.cpu().numpy(), roff)
     assert np.array_equal(ss.cpu().numpy()[:R], rss[:R]) and (ss.cpu().numpy()[R:] == -7).all()
     assert np.array_equal(s2r.cpu().numpy(), rs2r.reshape(-1))
+
+
+@pytest.mark.parametrize("T, N, Z, K, dtype", [(203, 70, 27, 6, "bf16"), (1, 3, 2, 5, "bf16"), (1000, 5, 0, 2, "bf16"),
+                                               (77, 7, 5, 3, "f32")])
+def test_token_zero_slots_against_the_oracle(T, N, Z, K, dtype):
+    # token-level zero-expert usage (Section 4.1): the ids the GPU router wrote, counted per token; overwrite, then
+    # accumulate a second time (the sum over two layers)
+    w = synth.Workload("tz", T=T, H=128, I=64, N=N, Z=Z, K=K, dtype=dtype, seed=57, recipe="zero_bias", wr_std=0.08,
+                       zero_bias=0.3)
+    print(w, flush=True)
+    L = harness.gapped_layer(w, "cuda")
+    d = desc_of(w)
+    ids = torch.empty((w.T, w.K), dtype=torch.int32, device="cuda")
+    gates = torch.empty((w.T, w.K), dtype=torch.float32, device="cuda")
+    zeda.zeda_route(d, L["x"], L["w_router"], L["router_bias"], ids, gates)
+    a = harness.to_arrays(L)
+    rid, _ = orc.route(a["x"], a["w_router"], a["router_bias"], w.N, w.Z, w.K)
+    ref = orc.token_zero_slots(rid, w.N)
+    zs = torch.full((w.T,), -9, dtype=torch.int32, device="cuda")
+    zeda.zeda_token_zero_slots(d, ids, zs)
+    torch.cuda.synchronize()
+    assert np.array_equal(zs.cpu().numpy(), ref)
+    zeda.zeda_token_zero_slots(d, ids, zs, accumulate=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(zs.cpu().numpy(), 2 * ref)
+    with pytest.raises(zeda.ZedaError):
+        zeda.zeda_token_zero_slots(d, None, zs)

@@ -375,6 +375,29 @@ def test_routing_stats_bias_moves_slots_to_the_zero_group():
         orc.routing_stats(L["x"], L["wr"], None, N, Z, K, w=0.0)
 
 
+def test_token_zero_slots_hand_case_and_what_it_must_add_up_to():
+    """Section 4.1's token-level r_ZE: a hand case, then, on a routed batch, two identities with functions that do
+    not share code with it - the real slots the counting sort places (T*K - sum = offsets[N]) and the batch r_ZE of
+    the Section 2.2 statistics (mean of the per-token shares)."""
+    ids = np.array([[0, 5, 2], [4, 3, 6], [1, 2, 0], [3, 3, 3]], dtype=np.int32)  # N = 3: ids >= 3 are zero experts
+    assert orc.token_zero_slots(ids, 3).tolist() == [1, 3, 0, 3]
+    assert orc.token_zero_slots(ids, 7).tolist() == [0, 0, 0, 0]
+    assert orc.token_zero_slots(ids[:0], 3).tolist() == []
+    N, Z, K = 6, 4, 3
+    L = _rand_layer(64, T=90, H=16, I=8, N=N, Z=Z, scale_r=0.4)
+    bias = np.zeros(N + Z, dtype=np.float32)
+    bias[N:] = 0.2
+    tid, _ = orc.route(L["x"], L["wr"], bias, N, Z, K)
+    z = orc.token_zero_slots(tid, N)
+    assert z.min() >= 0 and z.max() <= K and 0 < z.sum() < 90 * K
+    assert [sum(1 for e in row if e >= N) for row in tid.tolist()] == z.tolist()  # written out token by token
+    off, _, s2r = orc.dispatch(tid, N)
+    assert 90 * K - int(z.sum()) == int(off[N])
+    assert np.array_equal((s2r.reshape(90, K) < 0).sum(axis=1), z)
+    s = orc.routing_stats(L["x"], L["wr"], bias, N, Z, K)
+    assert float(np.mean(z / K)) == pytest.approx(s["r_ze"], rel=1e-12)
+
+
 # ----------------------------------------------------------------------------------------------
 # Router rows of the zero experts (Section 2.1, router initialisation)
 # ----------------------------------------------------------------------------------------------
