@@ -148,6 +148,38 @@ def stack_bench(a) -> int:
     return 0
 
 
+def overlap_probe(buf: torch.Tensor):
+    """How far this chip overlaps HBM streaming with matrix work: zeda_overlap_probe (four waves of every workgroup
+    stream 1 MiB, four others issue register-only MFMAs) timed with the reads alone, the MFMAs alone - their number
+    chosen so that both take about equally long - and both together, over the same buffer."""
+    nbytes = (buf.numel() * buf.element_size()) >> 20 << 20
+    flat = buf.view(-1).view(torch.uint8)[:nbytes]
+    sink = torch.empty((nbytes >> 20) * 256 + 1, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(mode, mfmas, reps=6):
+        for _ in range(2):
+            zeda.zeda_overlap_probe(flat, mfmas, mode, sink)
+        e0.record()
+        for _ in range(reps):
+            zeda.zeda_overlap_probe(flat, mfmas, mode, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+
+    t_read = timed(zeda.PROBE_READ, 0)
+    mfmas = 1600
+    mfmas = max(8, int(mfmas * t_read / timed(zeda.PROBE_MFMA, mfmas)) // 8 * 8)  # about as long as the reads
+    t_read, t_mfma, t_both = timed(zeda.PROBE_READ, 0), timed(zeda.PROBE_MFMA, mfmas), timed(zeda.PROBE_READ | zeda.PROBE_MFMA, mfmas)
+    wgs = nbytes >> 20
+    return {"bytes": nbytes, "mfmas_per_wave": mfmas, "read_alone_us": t_read, "mfma_alone_us": t_mfma, "both_us": t_both,
+            "read_alone_gbs": nbytes / (t_read * 1e-6) / 1e9,
+            "mfma_alone_tflops": 2.0 * 32 * 32 * 16 * mfmas * 4 * wgs / (t_mfma * 1e-6) / 1e12,
+            # share of the shorter part that running them together hides: 1 = perfect overlap, 0 = the times add up
+            "hidden_frac": (t_read + t_mfma - t_both) / min(t_read, t_mfma),
+            "note": "one kernel: waves 0-3 of every workgroup stream 1 MiB from HBM, waves 4-7 issue register-only MFMAs"}
+
+
 def pack_layer(w, L):
     """The layer with its expert weights in the library's tiled layout (packed once, as when a model is loaded)."""
     L = dict(L)
@@ -199,6 +231,7 @@ def other_config_legs(tiled: bool):
     legs["c4_hetero_prefill"] = {
         "T": w.T, "ms_per_step": r["wall_s"] / 150 * 1e3, "tokens_per_s": w.T * 150 / r["wall_s"],
         "real_slots": r["R"], "r_ze": 1.0 - r["R"] / (w.T * w.K), "max_rows_per_expert": r["max_rows"],
+        "nonempty_experts": r["nonempty"],
         "gateup_tflops": gu_f / gu_s / 1e12, "down_tflops": dn_f / dn_s / 1e12,
         "gateup_mfma_frac": gu_f / gu_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "expert_gemm_mfma_frac": (gu_f + dn_f) / (gu_s + dn_s) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
@@ -377,6 +410,20 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         mfma_tf = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        probe_buf = torch.randint(0, 2 ** 31 - 1, (1536 << 18,), dtype=torch.int32, device="cuda")  # 1.5 GiB: six MiB per CU
+        res["overlap_probe"] = overlap_probe(probe_buf)
+        del probe_buf
+
+        def chip_model_us(nbytes, nflops):
+            """Time the three yardsticks of this run give a kernel with these algorithmic bytes and FLOPs: the two parts
+            at the measured rates, added up, less the share of the shorter one that the overlap probe shows hidden."""
+            t_b, t_f = nbytes / (stream_gbs * 1e9), nflops / (mfma_tf * 1e12)
+            return (t_b + t_f - max(0.0, res["overlap_probe"]["hidden_frac"]) * min(t_b, t_f)) * 1e6
+
+        res["overlap_probe"]["gateup_model_us"] = chip_model_us(gu_bytes, gu_flops)
+        res["overlap_probe"]["gateup_measured_over_model"] = gu_s * 1e6 / res["overlap_probe"]["gateup_model_us"]
+        res["overlap_probe"]["down_model_us"] = chip_model_us(dn_bytes, dn_flops)
+        res["overlap_probe"]["down_measured_over_model"] = dn_s * 1e6 / res["overlap_probe"]["down_model_us"]
         res["mfma_probe"] = {"tflops": mfma_tf, "frac_of_peak": mfma_tf / MFMA_BF16_PEAK_TFLOPS,
                              "note": "zeda_mfma_probe: independent 32x32x16 bf16 MFMAs on register operands, nothing else; "
                                      "what the matrix units deliver on this machine without any data movement"}
@@ -422,6 +469,10 @@ def main() -> int:
         if "mfma_probe" in res:
             c4 = res["other_configs"]["c4_hetero_prefill"]
             c4["gateup_frac_of_mfma_probe"] = c4["gateup_tflops"] / res["mfma_probe"]["tflops"]
+            w4 = synth.CONFIGS["c4_hetero_prefill"]
+            b4 = 2.0 * w4.H * w4.I * 2 * c4["nonempty_experts"] + c4["real_slots"] * (w4.H + w4.I) * 2
+            c4["gateup_model_us"] = chip_model_us(b4, 4.0 * w4.H * w4.I * c4["real_slots"])
+            c4["gateup_measured_over_model"] = c4["stage_us"]["gateup"] / c4["gateup_model_us"]
 
     if not a.no_cpu_baseline:
         from oracle import harness, zeda_oracle as orc  # CPU-baseline leg only

@@ -271,6 +271,19 @@ int zeda_stream_read_probe(const void *buf, size_t bytes, void *sink, void *stre
  * that the work cannot be dropped.  ZEDA_EINVAL on NULL / unaligned sink, iters < 1, workgroups < 1. */
 int zeda_mfma_probe(int workgroups, int iters, float *sink, void *stream);
 
+/* Measurement aid, not part of the layer: both of the above in ONE kernel, to see how far the chip overlaps HBM
+ * streaming with matrix work.  Workgroups of eight waves; every workgroup owns 1 MiB of buf: its waves 0-3 read
+ * that MiB once (16-byte loads, sixteen per lane in flight), its waves 4-7 each issue mfmas_per_wave independent
+ * 32x32x16 bf16 MFMAs on register operands.  mode: ZEDA_PROBE_READ, ZEDA_PROBE_MFMA or both or-ed together (the
+ * waves of a part that is switched off exit at once).  bytes: a multiple of 1 MiB (bytes / 1 MiB workgroups);
+ * mfmas_per_wave >= 0, rounded down to a multiple of 8.  sink: device, (bytes / 1 MiB) * 256 floats (+ 1 word
+ * that is only written if the XOR of all words read equals an arbitrary constant).  Timed in its three modes on
+ * the same buffer, `both` = max(read, mfma) would be perfect overlap and `both` = read + mfma none at all;
+ * bench.py reports the three times.  ZEDA_EINVAL on NULL / unaligned pointers, bytes not a multiple of 1 MiB,
+ * mode outside 1..3, mfmas_per_wave < 0. */
+enum { ZEDA_PROBE_READ = 1, ZEDA_PROBE_MFMA = 2 };
+int zeda_overlap_probe(const void *buf, size_t bytes, int mfmas_per_wave, int mode, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

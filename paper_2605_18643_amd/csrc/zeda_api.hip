@@ -196,6 +196,53 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ sin
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// zeda_overlap_probe: waves 0-3 of a workgroup stream its 1 MiB, waves 4-7 run the register-only MFMA loop
+constexpr size_t kOverlapChunk = 1 << 20;
+template <bool READ, bool MFMA>
+__global__ __launch_bounds__(512) void overlap_probe_kernel(const u32x4 *__restrict__ p, int mfmas, float *__restrict__ sink,
+                                                            uint32_t *__restrict__ usink)
+{
+    const int wave = threadIdx.x >> 6;
+    if (wave < 4) {
+        if (!READ) return;
+        constexpr size_t chunk16 = kOverlapChunk / 16;
+        const u32x4 *q = p + (size_t)blockIdx.x * chunk16;
+        u32x4 acc = {0u, 0u, 0u, 0u};
+        for (size_t i = threadIdx.x; i < chunk16; i += 16 * 256) {
+            u32x4 v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = q[i + u * 256];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) acc ^= v[u];
+        }
+        if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x5eda5edau && (acc[0] + acc[1]) == 0x0badcafeu) *usink = acc[2];
+    } else {
+        if (!MFMA) return;
+        bf16x8 a, b;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t h = (threadIdx.x * 8u + i) * 2654435761u;
+            a[i] = (bf16_t)(((h >> 8) & 0xffff) / 32768.0f - 1.0f);
+            b[i] = (bf16_t)(((h >> 16) & 0xffff) / 32768.0f - 1.0f);
+        }
+        f32x16 acc[8];
+#pragma unroll
+        for (int n = 0; n < 8; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+        for (int it = 0; it < mfmas / 8; ++it) {
+#pragma unroll
+            for (int n = 0; n < 8; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n], 0, 0, 0);
+        }
+        float s = 0.f;
+#pragma unroll
+        for (int n = 0; n < 8; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s += acc[n][v];
+        sink[(size_t)blockIdx.x * 256 + (threadIdx.x - 256)] = s;
+    }
+}
+
 }  // namespace zeda
 
 using namespace zeda;
@@ -433,6 +480,23 @@ int zeda_mfma_probe(int workgroups, int iters, float *sink, void *stream)
 {
     if (!sink || (reinterpret_cast<uintptr_t>(sink) & 3u) || iters < 1 || workgroups < 1) return ZEDA_EINVAL;
     mfma_probe_kernel<<<(unsigned)workgroups, 256, 0, (hipStream_t)stream>>>(sink, iters);
+    return last_launch_status();
+}
+
+int zeda_overlap_probe(const void *buf, size_t bytes, int mfmas_per_wave, int mode, float *sink, void *stream)
+{
+    if (!buf || !sink || !aligned16(buf) || (reinterpret_cast<uintptr_t>(sink) & 3u) || (bytes % kOverlapChunk) != 0 ||
+        mode < 1 || mode > 3 || mfmas_per_wave < 0)
+        return ZEDA_EINVAL;
+    const size_t grid = bytes / kOverlapChunk;
+    if (grid == 0) return ZEDA_OK;
+    if (grid > 0x7fffffffu) return ZEDA_EUNSUPPORTED;
+    uint32_t *usink = reinterpret_cast<uint32_t *>(sink + grid * 256);
+    hipStream_t s = (hipStream_t)stream;
+    const u32x4 *p = (const u32x4 *)buf;
+    if (mode == ZEDA_PROBE_READ) overlap_probe_kernel<true, false><<<(unsigned)grid, 512, 0, s>>>(p, mfmas_per_wave, sink, usink);
+    else if (mode == ZEDA_PROBE_MFMA) overlap_probe_kernel<false, true><<<(unsigned)grid, 512, 0, s>>>(p, mfmas_per_wave, sink, usink);
+    else overlap_probe_kernel<true, true><<<(unsigned)grid, 512, 0, s>>>(p, mfmas_per_wave, sink, usink);
     return last_launch_status();
 }
 

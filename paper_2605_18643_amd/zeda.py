@@ -27,7 +27,7 @@ EXPORTS = ("zeda_status_string", "zeda_workspace_bytes", "zeda_route_workspace_b
            "zeda_expert_ffn", "zeda_combine", "zeda_moe_forward", "zeda_moe_forward_events", "zeda_moe_block_forward",
            "zeda_rmsnorm",
            "zeda_residual_add", "zeda_pack_expert_weights", "zeda_routing_stats_workspace_bytes", "zeda_routing_stats",
-           "zeda_init_zero_expert_rows", "zeda_stream_read_probe", "zeda_mfma_probe", "zeda_token_zero_slots")
+           "zeda_init_zero_expert_rows", "zeda_stream_read_probe", "zeda_mfma_probe", "zeda_token_zero_slots", "zeda_overlap_probe")
 
 
 class LayerDesc(ctypes.Structure):
@@ -95,6 +95,8 @@ def lib() -> ctypes.CDLL:
         L.zeda_init_zero_expert_rows.argtypes = [dp, vp, vp, vp, vp]
         L.zeda_token_zero_slots.restype = i32
         L.zeda_token_zero_slots.argtypes = [dp, vp, vp, i32, vp]
+        L.zeda_overlap_probe.restype = i32
+        L.zeda_overlap_probe.argtypes = [vp, sz, i32, i32, vp, vp]
         L.zeda_mfma_probe.restype = i32
         L.zeda_mfma_probe.argtypes = [i32, i32, vp, vp]
         L.zeda_stream_read_probe.restype = i32
@@ -235,6 +237,18 @@ def zeda_token_zero_slots(desc, topk_ids, zero_slots, accumulate: bool = False, 
     """zero_slots[t] (int32[T], device) = or += the number of token t's K slots on zero experts (Section 4.1)."""
     _check(lib().zeda_token_zero_slots(ctypes.byref(desc), _ptr(topk_ids), _ptr(zero_slots), int(bool(accumulate)),
                                        _stream(stream)), "zeda_token_zero_slots")
+
+
+PROBE_READ, PROBE_MFMA = 1, 2
+
+
+def zeda_overlap_probe(buf: torch.Tensor, mfmas_per_wave: int, mode: int, sink: torch.Tensor, stream=None) -> None:
+    """Measurement aid: streaming read of buf (a multiple of 1 MiB) and / or register-only MFMAs in one kernel.
+    sink: fp32, at least (MiB of buf) * 256 + 1 elements."""
+    nbytes = buf.numel() * buf.element_size()
+    assert sink.dtype == torch.float32 and sink.numel() >= (nbytes >> 20) * 256 + 1
+    _check(lib().zeda_overlap_probe(_ptr(buf), nbytes, int(mfmas_per_wave), int(mode), _ptr(sink), _stream(stream)),
+           "zeda_overlap_probe")
 
 
 def zeda_mfma_probe(workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> float:

@@ -148,3 +148,20 @@ def test_mfma_probe_runs_and_rejects_bad_arguments():
         with pytest.raises(zeda.ZedaError):
             zeda.lib()  # (argument checks run on the host)
             zeda._check(zeda.lib().zeda_mfma_probe(wg, it, zeda._ptr(sink), None), "zeda_mfma_probe")
+
+
+def test_overlap_probe_modes_and_bad_arguments():
+    buf = torch.arange((3 << 20) // 4, dtype=torch.int32, device="cuda")  # 3 MiB: three workgroups
+    sink = torch.zeros(3 * 256 + 1, dtype=torch.float32, device="cuda")
+    for mode in (zeda.PROBE_READ, zeda.PROBE_MFMA, zeda.PROBE_READ | zeda.PROBE_MFMA):
+        sink.zero_()
+        zeda.zeda_overlap_probe(buf, 16, mode, sink)
+        torch.cuda.synchronize()
+        wrote = float(sink[: 3 * 256].abs().sum())
+        assert (wrote > 0.0) == bool(mode & zeda.PROBE_MFMA)  # only the MFMA part leaves its sums
+        assert torch.isfinite(sink).all()
+    for bad in (dict(mode=0), dict(mode=4), dict(mfmas=-1)):
+        with pytest.raises(zeda.ZedaError):
+            zeda.zeda_overlap_probe(buf, bad.get("mfmas", 8), bad.get("mode", 3), sink)
+    with pytest.raises(zeda.ZedaError):
+        zeda._check(zeda.lib().zeda_overlap_probe(zeda._ptr(buf), (1 << 20) + 16, 8, 3, zeda._ptr(sink), None), "zeda_overlap_probe")
