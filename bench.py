@@ -149,12 +149,14 @@ def stack_bench(a) -> int:
 
 
 def overlap_probe(buf: torch.Tensor):
-    """How far this chip overlaps HBM streaming with matrix work: zeda_overlap_probe (four waves of every workgroup
-    stream 1 MiB, four others issue register-only MFMAs) timed with the reads alone, the MFMAs alone - their number
-    chosen so that both take about equally long - and both together, over the same buffer."""
+    """How far a CU overlaps HBM streaming with matrix work: zeda_overlap_probe timed with the reads alone, the MFMAs
+    alone - their number chosen so that both take about equally long - and both together, over the same buffer, for
+    its two placements of the waves (every SIMD holding a reading and a multiplying wave; the readers on a SIMD of
+    their own)."""
     nbytes = (buf.numel() * buf.element_size()) >> 20 << 20
     flat = buf.view(-1).view(torch.uint8)[:nbytes]
-    sink = torch.empty((nbytes >> 20) * 256 + 1, dtype=torch.float32, device="cuda")
+    wgs = nbytes >> 20
+    sink = torch.zeros(wgs * 512 + 8, dtype=torch.float32, device="cuda")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     def timed(mode, mfmas, reps=6):
@@ -165,19 +167,27 @@ def overlap_probe(buf: torch.Tensor):
             zeda.zeda_overlap_probe(flat, mfmas, mode, sink)
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps * 1e3
+        clk = sink[wgs * 512 + 2: wgs * 512 + 6].view(torch.int64).cpu().numpy()  # cycles, 100 MHz ticks (last launch)
+        return e0.elapsed_time(e1) / reps * 1e3, 100.0 * float(clk[0]) / max(1.0, float(clk[1]))
 
-    t_read = timed(zeda.PROBE_READ, 0)
-    mfmas = 1600
-    mfmas = max(8, int(mfmas * t_read / timed(zeda.PROBE_MFMA, mfmas)) // 8 * 8)  # about as long as the reads
-    t_read, t_mfma, t_both = timed(zeda.PROBE_READ, 0), timed(zeda.PROBE_MFMA, mfmas), timed(zeda.PROBE_READ | zeda.PROBE_MFMA, mfmas)
-    wgs = nbytes >> 20
-    return {"bytes": nbytes, "mfmas_per_wave": mfmas, "read_alone_us": t_read, "mfma_alone_us": t_mfma, "both_us": t_both,
-            "read_alone_gbs": nbytes / (t_read * 1e-6) / 1e9,
-            "mfma_alone_tflops": 2.0 * 32 * 32 * 16 * mfmas * 4 * wgs / (t_mfma * 1e-6) / 1e12,
-            # share of the shorter part that running them together hides: 1 = perfect overlap, 0 = the times add up
-            "hidden_frac": (t_read + t_mfma - t_both) / min(t_read, t_mfma),
-            "note": "one kernel: waves 0-3 of every workgroup stream 1 MiB from HBM, waves 4-7 issue register-only MFMAs"}
+    out = {"bytes": nbytes,
+           "note": "one kernel, one workgroup of eight waves per CU: some waves stream 1 MiB from HBM, the others issue "
+                   "register-only MFMAs; hidden_frac = (read + mfma - both) / min(read, mfma): 1 = perfect overlap, "
+                   "0 = the times add up"}
+    for name, place, n_mfma_waves in (("same_simd", 0, 4), ("split_simd", zeda.PROBE_SPLIT_SIMD, 6)):
+        t_read, _ = timed(zeda.PROBE_READ | place, 0)
+        mfmas = 1600
+        mfmas = max(8, int(mfmas * t_read / timed(zeda.PROBE_MFMA | place, mfmas)[0]) // 8 * 8)  # about as long as the reads
+        (t_read, mhz_read), (t_mfma, mhz_mfma), (t_both, mhz_both) = (
+            timed(zeda.PROBE_READ | place, 0), timed(zeda.PROBE_MFMA | place, mfmas),
+            timed(zeda.PROBE_READ | zeda.PROBE_MFMA | place, mfmas))
+        out[name] = {"mfmas_per_wave": mfmas, "mfma_waves": n_mfma_waves, "read_alone_us": t_read, "mfma_alone_us": t_mfma,
+                     "both_us": t_both, "read_alone_gbs": nbytes / (t_read * 1e-6) / 1e9,
+                     "mfma_alone_tflops": 2.0 * 32 * 32 * 16 * mfmas * n_mfma_waves * wgs / (t_mfma * 1e-6) / 1e12,
+                     "hidden_frac": (t_read + t_mfma - t_both) / min(t_read, t_mfma),
+                     # shader clock while each ran (cycle counter over 100 MHz counter, one mid-launch wave)
+                     "shader_clock_mhz": {"read_alone": mhz_read, "mfma_alone": mhz_mfma, "both": mhz_both}}
+    return out
 
 
 def pack_layer(w, L):
@@ -414,20 +424,6 @@ def main() -> int:
         res["overlap_probe"] = overlap_probe(probe_buf)
         del probe_buf
 
-        def chip_model_us(nbytes, nflops):
-            """Time the three yardsticks of this run give a kernel with these algorithmic bytes and FLOPs: the two parts
-            at the measured rates, added up, less the share of the shorter one that the overlap probe shows hidden."""
-            t_b, t_f = nbytes / (stream_gbs * 1e9), nflops / (mfma_tf * 1e12)
-            return (t_b + t_f - max(0.0, res["overlap_probe"]["hidden_frac"]) * min(t_b, t_f)) * 1e6
-
-        res["overlap_probe"]["gateup_model_us"] = chip_model_us(gu_bytes, gu_flops)
-        res["overlap_probe"]["gateup_measured_over_model"] = gu_s * 1e6 / res["overlap_probe"]["gateup_model_us"]
-        res["overlap_probe"]["down_model_us"] = chip_model_us(dn_bytes, dn_flops)
-        res["overlap_probe"]["down_measured_over_model"] = dn_s * 1e6 / res["overlap_probe"]["down_model_us"]
-        res["mfma_probe"] = {"tflops": mfma_tf, "frac_of_peak": mfma_tf / MFMA_BF16_PEAK_TFLOPS,
-                             "note": "zeda_mfma_probe: independent 32x32x16 bf16 MFMAs on register operands, nothing else; "
-                                     "what the matrix units deliver on this machine without any data movement"}
-
     if not a.no_z0 and w.Z > 0:
         # the same kernels on the static layer: no zero experts, top-K over the N normal experts only
         w0, L0 = static_twin(w, L)
@@ -469,10 +465,6 @@ def main() -> int:
         if "mfma_probe" in res:
             c4 = res["other_configs"]["c4_hetero_prefill"]
             c4["gateup_frac_of_mfma_probe"] = c4["gateup_tflops"] / res["mfma_probe"]["tflops"]
-            w4 = synth.CONFIGS["c4_hetero_prefill"]
-            b4 = 2.0 * w4.H * w4.I * 2 * c4["nonempty_experts"] + c4["real_slots"] * (w4.H + w4.I) * 2
-            c4["gateup_model_us"] = chip_model_us(b4, 4.0 * w4.H * w4.I * c4["real_slots"])
-            c4["gateup_measured_over_model"] = c4["stage_us"]["gateup"] / c4["gateup_model_us"]
 
     if not a.no_cpu_baseline:
         from oracle import harness, zeda_oracle as orc  # CPU-baseline leg only

@@ -271,17 +271,24 @@ int zeda_stream_read_probe(const void *buf, size_t bytes, void *sink, void *stre
  * that the work cannot be dropped.  ZEDA_EINVAL on NULL / unaligned sink, iters < 1, workgroups < 1. */
 int zeda_mfma_probe(int workgroups, int iters, float *sink, void *stream);
 
-/* Measurement aid, not part of the layer: both of the above in ONE kernel, to see how far the chip overlaps HBM
- * streaming with matrix work.  Workgroups of eight waves; every workgroup owns 1 MiB of buf: its waves 0-3 read
- * that MiB once (16-byte loads, sixteen per lane in flight), its waves 4-7 each issue mfmas_per_wave independent
- * 32x32x16 bf16 MFMAs on register operands.  mode: ZEDA_PROBE_READ, ZEDA_PROBE_MFMA or both or-ed together (the
- * waves of a part that is switched off exit at once).  bytes: a multiple of 1 MiB (bytes / 1 MiB workgroups);
- * mfmas_per_wave >= 0, rounded down to a multiple of 8.  sink: device, (bytes / 1 MiB) * 256 floats (+ 1 word
- * that is only written if the XOR of all words read equals an arbitrary constant).  Timed in its three modes on
- * the same buffer, `both` = max(read, mfma) would be perfect overlap and `both` = read + mfma none at all;
- * bench.py reports the three times.  ZEDA_EINVAL on NULL / unaligned pointers, bytes not a multiple of 1 MiB,
- * mode outside 1..3, mfmas_per_wave < 0. */
-enum { ZEDA_PROBE_READ = 1, ZEDA_PROBE_MFMA = 2 };
+/* Measurement aid, not part of the layer: both of the above in ONE kernel, to see how far a CU overlaps HBM
+ * streaming with matrix work and whether that depends on which waves do what.  Workgroups of eight waves, one per
+ * CU at a time (the hardware places wave w of a workgroup on SIMD w % 4); every workgroup owns 1 MiB of buf, which
+ * its reading waves read once (16-byte loads, 64 KiB in flight), while each of its multiplying waves issues
+ * mfmas_per_wave independent 32x32x16 bf16 MFMAs on register operands.
+ *   mode & ZEDA_PROBE_READ / ZEDA_PROBE_MFMA: which of the two parts runs (at least one; the waves of a part that is
+ *     switched off exit at once).
+ *   mode & ZEDA_PROBE_SPLIT_SIMD clear: waves 0-3 read and waves 4-7 multiply - every SIMD holds a wave of each kind.
+ *   mode & ZEDA_PROBE_SPLIT_SIMD set:   waves 3 and 7 (SIMD 3) read and the six others multiply - no SIMD holds both.
+ * bytes: a multiple of 1 MiB (bytes / 1 MiB workgroups); mfmas_per_wave >= 0, rounded down to a multiple of 8.
+ * sink: device, 8-byte aligned, (bytes / 1 MiB) * 512 floats followed by 8 more words: one that is only written if
+ * the XOR of all words read equals an arbitrary constant, one unused, and two int64 - shader-clock cycles and ticks
+ * of the constant 100 MHz counter that one wave of the workgroup in the middle of the grid counted around its own
+ * work (100 * cycles / ticks = the shader clock in MHz while the kernel ran).  Timed in its three parts on the same
+ * buffer, `both` = max(read, mfma) would be perfect overlap and `both` = read + mfma none at all; bench.py reports
+ * the times for both placements.  ZEDA_EINVAL on NULL / unaligned pointers, bytes not a multiple of 1 MiB, a mode
+ * without a part or outside 1..7, mfmas_per_wave < 0. */
+enum { ZEDA_PROBE_READ = 1, ZEDA_PROBE_MFMA = 2, ZEDA_PROBE_SPLIT_SIMD = 4 };
 int zeda_overlap_probe(const void *buf, size_t bytes, int mfmas_per_wave, int mode, float *sink, void *stream);
 
 #ifdef __cplusplus

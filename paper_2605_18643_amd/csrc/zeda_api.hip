@@ -196,26 +196,50 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ sin
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-// zeda_overlap_probe: waves 0-3 of a workgroup stream its 1 MiB, waves 4-7 run the register-only MFMA loop
+// zeda_overlap_probe.  Waves go to the four SIMDs of a CU round-robin (wave w runs on SIMD w % 4).  SPLIT false: waves
+// 0-3 stream, waves 4-7 multiply, so every SIMD holds one wave of each kind.  SPLIT true: waves 3 and 7 (SIMD 3) stream,
+// the six others multiply, so no SIMD holds both kinds.  The readers keep the same number of bytes in flight per
+// workgroup either way (64 KiB).  96 KiB of LDS that nobody touches hold the kernel to one workgroup per CU in every mode.
 constexpr size_t kOverlapChunk = 1 << 20;
-template <bool READ, bool MFMA>
+constexpr int kOverlapLds = 96 * 1024;
+template <bool READ, bool MFMA, bool SPLIT>
 __global__ __launch_bounds__(512) void overlap_probe_kernel(const u32x4 *__restrict__ p, int mfmas, float *__restrict__ sink,
                                                             uint32_t *__restrict__ usink)
 {
-    const int wave = threadIdx.x >> 6;
-    if (wave < 4) {
+    extern __shared__ unsigned char overlap_pad[];
+    if (mfmas < 0) overlap_pad[threadIdx.x] = 1;  // (never: keeps the allocation)
+    constexpr int RT = SPLIT ? 128 : 256;  // reading threads
+    constexpr int NLD = SPLIT ? 32 : 16;   // 16-byte loads of a lane in flight
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const bool reader = SPLIT ? (wave & 3) == 3 : wave < 4;
+    const int rtid = SPLIT ? (wave >> 2) * 64 + lane : (int)threadIdx.x;
+    // one wave of each kind in the workgroup in the middle of the grid reads the cycle counter and the 100 MHz counter
+    // around its work (readers report if there are readers, else the multiplying wave does)
+    const bool rec = blockIdx.x == (gridDim.x >> 1) && lane == 0 && (READ ? (reader && rtid == 0) : wave == (SPLIT ? 0 : 4));
+    long long c0 = 0, r0 = 0;
+    if (blockIdx.x == (gridDim.x >> 1)) {
+        c0 = __builtin_amdgcn_s_memtime();
+        r0 = __builtin_amdgcn_s_memrealtime();
+    }
+    long long *clk = reinterpret_cast<long long *>(usink + 2);
+    if (reader) {
         if (!READ) return;
         constexpr size_t chunk16 = kOverlapChunk / 16;
+        static_assert(chunk16 % (NLD * RT) == 0, "a workgroup's loads stay inside its MiB");
         const u32x4 *q = p + (size_t)blockIdx.x * chunk16;
         u32x4 acc = {0u, 0u, 0u, 0u};
-        for (size_t i = threadIdx.x; i < chunk16; i += 16 * 256) {
-            u32x4 v[16];
+        for (size_t i = rtid; i < chunk16; i += NLD * RT) {
+            u32x4 v[NLD];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) v[u] = q[i + u * 256];
+            for (int u = 0; u < NLD; ++u) v[u] = q[i + u * RT];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) acc ^= v[u];
+            for (int u = 0; u < NLD; ++u) acc ^= v[u];
         }
         if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x5eda5edau && (acc[0] + acc[1]) == 0x0badcafeu) *usink = acc[2];
+        if (rec) {
+            clk[0] = __builtin_amdgcn_s_memtime() - c0 + (long long)(acc[0] & 0u);  // (after the loads have landed)
+            clk[1] = __builtin_amdgcn_s_memrealtime() - r0;
+        }
     } else {
         if (!MFMA) return;
         bf16x8 a, b;
@@ -239,8 +263,28 @@ __global__ __launch_bounds__(512) void overlap_probe_kernel(const u32x4 *__restr
         for (int n = 0; n < 8; ++n)
 #pragma unroll
             for (int v = 0; v < 16; ++v) s += acc[n][v];
-        sink[(size_t)blockIdx.x * 256 + (threadIdx.x - 256)] = s;
+        sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+        if (rec) {
+            clk[0] = __builtin_amdgcn_s_memtime() - c0 + (long long)(s != s ? 1 : 0);  // (after the MFMAs have finished)
+            clk[1] = __builtin_amdgcn_s_memrealtime() - r0;
+        }
     }
+}
+
+template <bool READ, bool MFMA, bool SPLIT>
+static int launch_overlap_probe(const u32x4 *p, size_t grid, int mfmas, float *sink, uint32_t *usink, hipStream_t s)
+{
+    static bool done[kMaxDevices] = {};  // per instantiation and device (idempotent)
+    const int dev = current_device();
+    if (dev < 0) return ZEDA_EHIP;
+    if (!done[dev]) {
+        if (hipFuncSetAttribute((const void *)overlap_probe_kernel<READ, MFMA, SPLIT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kOverlapLds) != hipSuccess)
+            return ZEDA_EHIP;
+        done[dev] = true;
+    }
+    overlap_probe_kernel<READ, MFMA, SPLIT><<<(unsigned)grid, 512, kOverlapLds, s>>>(p, mfmas, sink, usink);
+    return last_launch_status();
 }
 
 }  // namespace zeda
@@ -485,19 +529,25 @@ int zeda_mfma_probe(int workgroups, int iters, float *sink, void *stream)
 
 int zeda_overlap_probe(const void *buf, size_t bytes, int mfmas_per_wave, int mode, float *sink, void *stream)
 {
-    if (!buf || !sink || !aligned16(buf) || (reinterpret_cast<uintptr_t>(sink) & 3u) || (bytes % kOverlapChunk) != 0 ||
-        mode < 1 || mode > 3 || mfmas_per_wave < 0)
+    const int what = mode & (ZEDA_PROBE_READ | ZEDA_PROBE_MFMA);
+    if (!buf || !sink || !aligned16(buf) || (reinterpret_cast<uintptr_t>(sink) & 7u) || (bytes % kOverlapChunk) != 0 ||
+        mode < 1 || mode > 7 || what == 0 || mfmas_per_wave < 0)
         return ZEDA_EINVAL;
     const size_t grid = bytes / kOverlapChunk;
     if (grid == 0) return ZEDA_OK;
     if (grid > 0x7fffffffu) return ZEDA_EUNSUPPORTED;
-    uint32_t *usink = reinterpret_cast<uint32_t *>(sink + grid * 256);
+    uint32_t *usink = reinterpret_cast<uint32_t *>(sink + grid * 512);
     hipStream_t s = (hipStream_t)stream;
     const u32x4 *p = (const u32x4 *)buf;
-    if (mode == ZEDA_PROBE_READ) overlap_probe_kernel<true, false><<<(unsigned)grid, 512, 0, s>>>(p, mfmas_per_wave, sink, usink);
-    else if (mode == ZEDA_PROBE_MFMA) overlap_probe_kernel<false, true><<<(unsigned)grid, 512, 0, s>>>(p, mfmas_per_wave, sink, usink);
-    else overlap_probe_kernel<true, true><<<(unsigned)grid, 512, 0, s>>>(p, mfmas_per_wave, sink, usink);
-    return last_launch_status();
+    const bool split = (mode & ZEDA_PROBE_SPLIT_SIMD) != 0;
+    if (what == ZEDA_PROBE_READ)
+        return split ? launch_overlap_probe<true, false, true>(p, grid, mfmas_per_wave, sink, usink, s)
+                     : launch_overlap_probe<true, false, false>(p, grid, mfmas_per_wave, sink, usink, s);
+    if (what == ZEDA_PROBE_MFMA)
+        return split ? launch_overlap_probe<false, true, true>(p, grid, mfmas_per_wave, sink, usink, s)
+                     : launch_overlap_probe<false, true, false>(p, grid, mfmas_per_wave, sink, usink, s);
+    return split ? launch_overlap_probe<true, true, true>(p, grid, mfmas_per_wave, sink, usink, s)
+                 : launch_overlap_probe<true, true, false>(p, grid, mfmas_per_wave, sink, usink, s);
 }
 
 }  // extern "C"

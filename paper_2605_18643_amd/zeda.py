@@ -239,14 +239,15 @@ def zeda_token_zero_slots(desc, topk_ids, zero_slots, accumulate: bool = False, 
                                        _stream(stream)), "zeda_token_zero_slots")
 
 
-PROBE_READ, PROBE_MFMA = 1, 2
+PROBE_READ, PROBE_MFMA, PROBE_SPLIT_SIMD = 1, 2, 4
 
 
 def zeda_overlap_probe(buf: torch.Tensor, mfmas_per_wave: int, mode: int, sink: torch.Tensor, stream=None) -> None:
     """Measurement aid: streaming read of buf (a multiple of 1 MiB) and / or register-only MFMAs in one kernel.
-    sink: fp32, at least (MiB of buf) * 256 + 1 elements."""
+    sink: fp32, at least (MiB of buf) * 512 + 8 elements; the last six of these hold two int64 (shader-clock cycles
+    and 100 MHz ticks of one mid-launch wave)."""
     nbytes = buf.numel() * buf.element_size()
-    assert sink.dtype == torch.float32 and sink.numel() >= (nbytes >> 20) * 256 + 1
+    assert sink.dtype == torch.float32 and sink.numel() >= (nbytes >> 20) * 512 + 8
     _check(lib().zeda_overlap_probe(_ptr(buf), nbytes, int(mfmas_per_wave), int(mode), _ptr(sink), _stream(stream)),
            "zeda_overlap_probe")
 

@@ -152,15 +152,20 @@ def test_mfma_probe_runs_and_rejects_bad_arguments():
 
 def test_overlap_probe_modes_and_bad_arguments():
     buf = torch.arange((3 << 20) // 4, dtype=torch.int32, device="cuda")  # 3 MiB: three workgroups
-    sink = torch.zeros(3 * 256 + 1, dtype=torch.float32, device="cuda")
-    for mode in (zeda.PROBE_READ, zeda.PROBE_MFMA, zeda.PROBE_READ | zeda.PROBE_MFMA):
-        sink.zero_()
-        zeda.zeda_overlap_probe(buf, 16, mode, sink)
-        torch.cuda.synchronize()
-        wrote = float(sink[: 3 * 256].abs().sum())
-        assert (wrote > 0.0) == bool(mode & zeda.PROBE_MFMA)  # only the MFMA part leaves its sums
-        assert torch.isfinite(sink).all()
-    for bad in (dict(mode=0), dict(mode=4), dict(mfmas=-1)):
+    n = 3 * 512
+    sink = torch.zeros(n + 8, dtype=torch.float32, device="cuda")
+    for place in (0, zeda.PROBE_SPLIT_SIMD):
+        for mode in (zeda.PROBE_READ, zeda.PROBE_MFMA, zeda.PROBE_READ | zeda.PROBE_MFMA):
+            sink.zero_()
+            zeda.zeda_overlap_probe(buf, 800, mode | place, sink)
+            torch.cuda.synchronize()
+            wrote = int((sink[:n] != 0).sum())
+            # only the multiplying waves leave their sums: four of eight waves, or six with the readers on a SIMD of their own
+            assert wrote == (0 if not mode & zeda.PROBE_MFMA else 3 * 64 * (6 if place else 4)), (mode, place, wrote)
+            assert torch.isfinite(sink[: n + 2]).all()
+            cycles, ticks = (int(v) for v in sink[n + 2: n + 6].view(torch.int64).cpu())
+            assert cycles > 0 and ticks > 0 and 100.0 < 100.0 * cycles / ticks < 3000.0  # a plausible shader clock
+    for bad in (dict(mode=0), dict(mode=4), dict(mode=8), dict(mfmas=-1)):
         with pytest.raises(zeda.ZedaError):
             zeda.zeda_overlap_probe(buf, bad.get("mfmas", 8), bad.get("mode", 3), sink)
     with pytest.raises(zeda.ZedaError):
