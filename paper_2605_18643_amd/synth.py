@@ -20,7 +20,6 @@ zero experts (Section 3.2 reports r_ZE of 51.2 %), token-level heterogeneity
 from __future__ import annotations
 
 import dataclasses
-import math
 from typing import Dict, Optional
 
 import numpy as np
