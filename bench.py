@@ -267,6 +267,9 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload (sequence-length sweeps)")
     ap.add_argument("--weights", default="tiled", choices=["tiled", "row_major"],
                     help="storage of the expert weights: packed once into the library's tiled layout (default), or row-major")
+    ap.add_argument("--token-sweep", default="",
+                    help="comma-separated token counts: times the workload's layer and its Z=0 twin at each of them "
+                         "(sequence-length sweep) and prints one JSON line with the table; nothing else is run")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one plain elementwise kernel that reads and writes 2^28 bytes (a yardstick for "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters; outside the timed region)")
@@ -309,6 +312,27 @@ def main() -> int:
         return stack_bench(a)
 
     w = synth.CONFIGS[a.workload]
+    if a.token_sweep:
+        rows = []
+        for T in (int(v) for v in a.token_sweep.split(",")):
+            wt = w.with_(T=T)
+            Lt = synth.make_layer(wt, "cuda")
+            if a.weights == "tiled" and wt.dtype == "bf16":
+                Lt = pack_layer(wt, Lt)
+            steps = max(20, min(400, (1 << 21) // T))
+            r = run_layer(wt, Lt, steps, steps // 4, lead_in=(steps, steps // 4))
+            w0, L0 = static_twin(wt, Lt)
+            r0 = run_layer(w0, L0, steps, steps // 4, lead_in=(steps, steps // 4))
+            rows.append({"T": T, "steps": steps, "us_per_step": r["wall_s"] / steps * 1e6,
+                         "tokens_per_s": T * steps / r["wall_s"], "z0_us_per_step": r0["wall_s"] / steps * 1e6,
+                         "speedup_vs_z0": r0["wall_s"] / r["wall_s"], "r_ze": 1.0 - r["R"] / (T * wt.K),
+                         "rows_per_expert": r["R"] / max(1, r["nonempty"]),
+                         "stage_us": {k: float(v) * 1e3 for k, v in zip(zeda.STAGES, r["stage_ms"])}})
+            del Lt, L0
+            torch.cuda.empty_cache()
+        print(json.dumps({"token_sweep": rows, "workload": w.name, "weight_layout": a.weights, "dtype": w.dtype,
+                          "data": "synthetic"}))
+        return 0
     if a.tokens > 0:
         w = w.with_(T=a.tokens)
     L = synth.make_layer(w, "cuda")
